@@ -1,0 +1,290 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE expert layer hot path on one MI355X.
+
+A step = one pass of the whole hot path (moe_route -> moe_permute ->
+moe_expert_ffn -> moe_combine, through the C ABI) over one batch of synthetic,
+Mixtral-8x7B-shaped input that is already resident in HBM.  Steps rotate over
+several independent weight sets (layers) and inputs so that no step finds its
+expert matrices in the last-level cache.
+
+Prints ONE JSON line: whole-job tokens/s, plus
+  roofline     -- the dominant kernel (first projection of moe_expert_ffn) timed
+                  live with HIP events on the launch stream, against HBM peak
+                  (decode-sized workloads) or bf16 MFMA peak (prefill);
+  cpu_baseline -- the fp64 CPU oracle timed on this machine's host cores on a
+                  bounded sample of the same workload (a baseline, not a target).
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+WORKLOADS = {
+    # name: (T, x dtype, zipf skew of the router logits, bound)
+    "decode_t1": dict(T=1, x_bf16=False, zipf=None, bound="hbm"),
+    "beam_t16": dict(T=16, x_bf16=False, zipf=1.2, bound="hbm"),
+    "prefill_t4096": dict(T=4096, x_bf16=True, zipf=1.2, bound="mfma"),
+}
+D, F, E, K = 4096, 14336, 8, 2
+
+
+class HipEvents:
+    """Minimal HIP event wrapper (torch.cuda.Event only sees torch's stream API;
+    these are recorded on the raw stream handle the library launches on)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self) -> int:
+        ev = C.c_void_p()
+        assert self.hip.hipEventCreate(C.byref(ev)) == 0
+        return ev.value
+
+    def record(self, ev: int, stream: int):
+        assert self.hip.hipEventRecord(C.c_void_p(ev), C.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        assert self.hip.hipEventSynchronize(C.c_void_p(b)) == 0
+        ms = C.c_float()
+        assert self.hip.hipEventElapsedTime(C.byref(ms), C.c_void_p(a), C.c_void_p(b)) == 0
+        return float(ms.value)
+
+    def destroy(self, ev: int):
+        self.hip.hipEventDestroy(C.c_void_p(ev))
+
+
+def make_weight_set(torch, moe, seed):
+    """Random-init bf16 expert matrices N(0, 1/fan_in), generated on the device
+    (seeded torch generator), packed; returns (PackedWeights, host copy or None)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    w1 = torch.empty((E, D, F), dtype=torch.bfloat16, device="cuda")
+    w3 = torch.empty((E, D, F), dtype=torch.bfloat16, device="cuda")
+    w2 = torch.empty((E, F, D), dtype=torch.bfloat16, device="cuda")
+    for e in range(E):
+        w1[e] = (torch.randn((D, F), generator=g, device="cuda") * D ** -0.5).to(torch.bfloat16)
+        w3[e] = (torch.randn((D, F), generator=g, device="cuda") * D ** -0.5).to(torch.bfloat16)
+        w2[e] = (torch.randn((F, D), generator=g, device="cuda") * F ** -0.5).to(torch.bfloat16)
+    W = moe.moe_weights_pack(w1, w3, w2)
+    torch.cuda.synchronize()
+    return W, (w1, w3, w2)
+
+
+def make_inputs(torch, moe, wl, n_inputs, seed):
+    import numpy as np
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    T = wl["T"]
+    xs, lgs = [], []
+    wg = torch.randn((D, E), generator=g, device="cuda") * D ** -0.5
+    if wl["zipf"]:
+        r = np.arange(1, E + 1, dtype=np.float64) ** (-wl["zipf"])
+        bias = torch.tensor(np.log(r / r.sum()), dtype=torch.float32, device="cuda")
+    for _ in range(n_inputs):
+        x = torch.randn((T, D), generator=g, device="cuda")
+        if wl["zipf"]:
+            lg = torch.randn((T, E), generator=g, device="cuda") + bias[None, :]
+        else:
+            lg = moe.moe_router_logits(x, wg)
+        if wl["x_bf16"]:
+            x = x.to(torch.bfloat16)
+        xs.append(x.contiguous())
+        lgs.append(lg.contiguous())
+    torch.cuda.synchronize()
+    return xs, lgs
+
+
+class Step:
+    """Preallocated buffers + the four C-ABI calls of one step."""
+
+    def __init__(self, torch, moe, T, x_dtype):
+        N = T * K
+        i32 = dict(dtype=torch.int32, device="cuda")
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.moe = moe
+        self.idx = torch.empty((T, K), **i32)
+        self.w = torch.empty((T, K), **f32)
+        self.perm_out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
+                         torch.empty(N, **i32), torch.empty((N, D), dtype=x_dtype, device="cuda"))
+        adt = moe.MOE_BF16 if x_dtype == torch.bfloat16 else moe.MOE_F32
+        self.ws = torch.empty(moe.moe_expert_ffn_workspace(N, E, D, F, adt), dtype=torch.uint8,
+                              device="cuda")
+        self.yg = torch.empty((N, D), **f32)
+        self.y = torch.empty((T, D), **f32)
+
+    def run(self, W, x, logits, ev=None, events=None, stream=0):
+        moe = self.moe
+        moe.moe_route(logits, K, self.idx, self.w)
+        counts, offsets, perm, inv_perm, xg = moe.moe_permute(self.idx, E, x, out=self.perm_out)
+        if ev is not None:
+            events.record(ev[0], stream)
+        moe.moe_expert_ffn(W, xg, offsets, workspace=self.ws, yg=self.yg)
+        if ev is not None:
+            events.record(ev[2], stream)
+        moe.moe_combine(self.yg, inv_perm, self.w, self.y)
+
+
+def cpu_baseline(torch, wl, host_w, xs, lgs, budget_s=15.0):
+    """The fp64 oracle, as it stands, on a bounded sample of this workload."""
+    import numpy as np
+    from oracle import moe_oracle as orc
+
+    def host(t):
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy()
+
+    def f64(a):
+        if a.dtype == np.uint16:
+            return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        return a.astype(np.float64)
+
+    w1, w3, w2 = (host(t) for t in host_w)
+    T = wl["T"]
+    done_tokens, t_used, i = 0, 0.0, 0
+    per_call = max(1, min(T, 4))  # tokens per oracle call
+    t_start = time.perf_counter()
+    while True:
+        x = f64(host(xs[i % len(xs)]))[:per_call]
+        lg = host(lgs[i % len(lgs)])[:per_call]
+        t0 = time.perf_counter()
+        orc.layer(x, lg, w1, w3, w2, K)
+        t_used += time.perf_counter() - t0
+        done_tokens += per_call
+        i += 1
+        if time.perf_counter() - t_start > budget_s or done_tokens >= 256:
+            break
+    return dict(value=done_tokens / t_used, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"{done_tokens} tokens of this workload, {per_call} per oracle call, "
+                       f"one weight set, {t_used:.1f} s of fp64 CPU work")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="decode_t1", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+                 "use --gpus 1")
+
+    import torch
+    import paper_2402_07033_amd as moe
+    moe.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    wl = WORKLOADS[args.workload]
+    T = wl["T"]
+    decode_like = wl["bound"] == "hbm"
+    steps = args.steps if args.steps is not None else (400 if decode_like else 30)
+    warmup = args.warmup if args.warmup is not None else (40 if decode_like else 5)
+    n_layers = args.layers if args.layers is not None else (8 if decode_like else 2)
+    n_inputs = 16 if decode_like else 2
+
+    sets, host_w = [], None
+    for li in range(n_layers):
+        W, src = make_weight_set(torch, moe, 2000 + li)
+        if li == 0 and not args.no_cpu_baseline:
+            host_w = tuple(t.cpu() for t in src)
+        del src
+        sets.append(W)
+    torch.cuda.empty_cache()
+    xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
+    step = Step(torch, moe, T, xs[0].dtype)
+    stream = torch.cuda.current_stream().cuda_stream
+    events = HipEvents()
+
+    def run_range(n, ev_list=None):
+        for i in range(n):
+            ev = ev_list[i] if ev_list is not None else None
+            if ev is not None:
+                moe.moe_set_ffn_mid_event(ev[1])
+            step.run(sets[i % n_layers], xs[i % n_inputs], lgs[i % n_inputs], ev, events, stream)
+
+    # realised per-expert counts of every input (outside any timed region)
+    counts_all = []
+    for i in range(n_inputs):
+        step.run(sets[0], xs[i], lgs[i])
+        torch.cuda.synchronize()
+        counts_all.append(step.perm_out[0].cpu().tolist())
+
+    run_range(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_range(steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    # second pass: HIP events around the two projection kernels of every step
+    ev_list = [(events.create(), events.create(), events.create()) for _ in range(steps)]
+    run_range(steps, ev_list)
+    moe.moe_set_ffn_mid_event(None)
+    torch.cuda.synchronize()
+    up_ms = sum(events.elapsed_ms(a, b) for a, b, _ in ev_list) / steps
+    dn_ms = sum(events.elapsed_ms(b, c) for _, b, c in ev_list) / steps
+    for ev in ev_list:
+        for e in ev:
+            events.destroy(e)
+
+    # algorithmic work of the dominant kernel (first projection), averaged over the steps
+    act_sets = [sum(1 for c in counts_all[i % n_inputs] if c > 0) for i in range(steps)]
+    n_active = sum(act_sets) / steps
+    if decode_like:
+        # bytes: w1 and w3 of every active expert, read once (2 * d * f bf16 each)
+        up_bytes = n_active * 2 * D * F * 2
+        achieved = up_bytes / (up_ms * 1e-3) / 1e9
+        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=achieved / HBM_PEAK_GBS, traffic=None,
+                        kernel="stream_kernel<KSW=16,NMAT=2> (x.w1, x.w3, silu*mul)",
+                        kernel_ms=up_ms, second_projection_ms=dn_ms,
+                        second_projection_GBs=n_active * D * F * 2 / (dn_ms * 1e-3) / 1e9,
+                        mean_active_experts=n_active)
+    else:
+        up_flops = T * K * 2 * 2 * D * F  # real rows only
+        achieved = up_flops / (up_ms * 1e-3) / 1e12
+        roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
+                        unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                        kernel="gg_pack + gg_gemm_kernel<UP> (x.w1, x.w3, silu*mul)",
+                        kernel_ms=up_ms, second_projection_ms=dn_ms,
+                        second_projection_TFLOPs=T * K * 2 * D * F / (dn_ms * 1e-3) / 1e12,
+                        layer_TFLOPs=T * K * 6 * D * F / (ms_per_step * 1e-3) / 1e12)
+
+    result = {
+        "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights x " + ("bf16" if wl["x_bf16"] else "fp32 (bf16 hi+lo)") +
+                 " activations, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "d_model": D, "d_ff": F, "experts": E,
+                   "top_k": K, "weight_sets_rotated": n_layers, "inputs_rotated": n_inputs,
+                   "counts_first_input": counts_all[0]},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(torch, wl, host_w, xs, lgs)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

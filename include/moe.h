@@ -1,0 +1,173 @@
+/*
+ * libmoe_hip -- C ABI of the MoE expert-layer hot path for AMD MI355X (gfx950).
+ *
+ * The layer is the computation Fiddler (arXiv 2402.07033) schedules: the
+ * gating function selects the experts of every token (Sec. 2.1, Sec. 3.3
+ * "Execution"), tokens are batched per expert (the inp_size array of
+ * Algorithm 1), every expert that received tokens runs its feed-forward block
+ * (three d x f matrices per expert, Sec. 3.2; SiLU activation, Sec. 2.2;
+ * experts with zero tokens are skipped, Algorithm 1), and the expert outputs
+ * return to the token stream.  All experts are resident in device memory,
+ * i.e. every expert is case (a) of Sec. 3.2.
+ *
+ * Conventions (all entry points):
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless the
+ *     comment says HOST.  The library never frees caller memory and allocates
+ *     device memory only in moe_weights_pack (released by moe_weights_free).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return; there is no host synchronisation
+ *     and no device-to-host copy inside any call except where stated.
+ *   - Return value: MOE_OK (0) or a negative moe_status_t.  Arguments are
+ *     validated on the host before anything is launched; on error nothing has
+ *     been enqueued.  No exception or abort crosses the boundary.
+ *   - Row-major arrays; pointers must be 16-byte aligned.
+ *   - Domain: 1 <= k <= 8, k <= E <= 64, T >= 0 (T == 0 is a no-op),
+ *     T*k < 2^24, d and f multiples of 64.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1, /* null/misaligned pointer, size out of the domain */
+    MOE_ERR_UNSUPPORTED = -2, /* valid request this build has no kernel for */
+    MOE_ERR_WORKSPACE = -3,   /* workspace missing or too small */
+    MOE_ERR_HIP = -4          /* a HIP runtime call failed (allocation, launch) */
+} moe_status_t;
+
+/* Which expert-FFN kernels to run.  AUTO picks from N and the shape. */
+typedef enum {
+    MOE_FFN_AUTO = 0,
+    MOE_FFN_STREAM = 1, /* decode: weight-streaming MFMA kernels, <=16 rows per pass */
+    MOE_FFN_GROUPED = 2 /* prefill: grouped LDS-tiled MFMA GEMM */
+} moe_ffn_path_t;
+
+typedef struct moe_weights moe_weights_t; /* opaque, library-owned */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* moe_status_string(int status);
+
+/*
+ * Gating (Sec. 2.1; Sec. 3.3 "Execution": the gating function tells which
+ * experts each token uses).  For every token t the k largest of logits[t,:]
+ * are selected on the raw fp32 values; a larger logit comes first and among
+ * equal logits (+0.0 == -0.0) the lower expert index comes first.  weights is
+ * the softmax over the k selected logits (the full softmax renormalised over
+ * the winners), fp32.
+ *   logits  [T,E] fp32, finite (NaN/Inf: result unspecified)
+ *   idx     [T,k] int32 out, expert ids in the order described above
+ *   weights [T,k] fp32 out
+ */
+int moe_route(const float* logits, int T, int E, int k, int32_t* idx, float* weights,
+              void* stream);
+
+/*
+ * Per-expert batching (Algorithm 1's inp_size; Sec. 3.3).  With flat slots
+ * p = t*k + j and e_p = idx[p]:
+ *   counts[e]  = number of slots routed to e          (inp_size)
+ *   offsets    = exclusive scan of counts, offsets[E] = T*k
+ *   perm       = stable ordering of the slots by expert: perm[i] = p
+ *   inv_perm   = its inverse: inv_perm[p] = i
+ *   xg[i,:]    = x[perm[i] / k, :]  (bit copy, same dtype as x)
+ * All index outputs are int32 and unique, hence bit-reproducible.
+ *   idx [T,k] int32 with 0 <= idx < E (values outside are undefined behaviour
+ *   of the outputs but never of memory: they are clamped for addressing)
+ *   x   [T,d] of x_dtype, xg [T*k,d] out; x and xg may both be NULL to skip
+ *   the row gather.
+ */
+int moe_permute(const int32_t* idx, int T, int E, int k, const void* x, int d,
+                moe_dtype_t x_dtype, int32_t* counts, int32_t* offsets, int32_t* perm,
+                int32_t* inv_perm, void* xg, void* stream);
+
+/*
+ * One-time repack of a layer's expert matrices (Sec. 3.2: w1, w3 [d,f] and
+ * w2 [f,d] per expert, stacked over experts; y = (silu(x.w1) * (x.w3)) . w2)
+ * into the layout the kernels stream.  The sources are read on `stream` and
+ * may be freed once the stream has passed this call.
+ *   w_dtype MOE_BF16: device copy in MFMA-fragment order, same byte count.
+ *   w_dtype MOE_F32 : plain device copy.
+ * *out receives a handle owned by the library; release with moe_weights_free
+ * (which synchronises the device).  Allocates device memory.
+ */
+int moe_weights_pack(const void* w1, const void* w3, const void* w2, int E, int d, int f,
+                     moe_dtype_t w_dtype, moe_weights_t** out, void* stream);
+int moe_weights_free(moe_weights_t* w);
+/* Device bytes held by a packed handle (0 for NULL). HOST query. */
+size_t moe_weights_bytes(const moe_weights_t* w);
+
+/* Bytes of scratch moe_expert_ffn needs for N rows (any path). HOST query;
+ * returns 0 for arguments outside the domain. */
+size_t moe_expert_ffn_workspace(int N, int E, int d, int f, moe_dtype_t act_dtype);
+
+/*
+ * Expert feed-forward over the batched rows (Sec. 3.2 case (a); Algorithm 1
+ * loop over experts, skipping empty ones).  For each expert e and each row i
+ * in [offsets[e], offsets[e+1]):
+ *     yg[i,:] = ( silu(xg[i,:] . w1_e) * (xg[i,:] . w3_e) ) . w2_e
+ * with fp32 accumulation.  offsets is read on the device: the call never
+ * learns the per-expert sizes on the host.
+ *   W         packed handle (bf16 or fp32 weights)
+ *   xg        [N,d] of act_dtype (fp32 weights need fp32 activations)
+ *   offsets   [E+1] int32 DEVICE, offsets[0] = 0, non-decreasing, offsets[E] = N
+ *   workspace >= moe_expert_ffn_workspace(...) bytes, 256-byte aligned; contents
+ *             are scratch (may be reused by the next call on the same stream)
+ *   yg        [N,d] fp32 out
+ * bf16-weight kernels multiply on the bf16 matrix cores: fp32 activations are
+ * split into bf16 high and low parts (STREAM path, ~2^-16 relative) or rounded
+ * to bf16 (GROUPED path); the intermediate silu(a)*b is kept in fp32 (STREAM)
+ * or bf16 (GROUPED).  The STREAM path adds partial sums of the second
+ * projection with fp32 atomics, so its low-order bits may differ run to run.
+ */
+int moe_expert_ffn(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                   const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
+                   float* yg, void* stream);
+/* Same, with the kernel family forced (for tests and measurements).  Returns
+ * MOE_ERR_UNSUPPORTED if that family cannot run the shape. */
+int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                        const int32_t* offsets, int N, void* workspace,
+                        size_t workspace_bytes, float* yg, int path, void* stream);
+
+/*
+ * Expert outputs return to token order, weighted by the gate (Sec. 3.2 names
+ * the return of expert outputs; the weighting is the Mixtral layer's):
+ *     y[t,:] = sum_{j=0..k-1, ascending} weights[t,j] * yg[inv_perm[t*k+j], :]
+ *   yg [T*k,d] fp32, inv_perm [T*k] int32, weights [T,k] fp32, y [T,d] fp32 out
+ */
+int moe_combine(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
+                int d, float* y, void* stream);
+
+/*
+ * Support steps of the layer-stack workload (non-expert glue the paper keeps
+ * on the GPU, Sec. 3.1): RMS normalisation without gain, router logits and the
+ * residual add.
+ *   moe_rmsnorm:       h[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + eps)    fp32 [T,d]
+ *   moe_router_logits: logits[t,e] = sum_r h[t,r] * w_gate[r,e]        w_gate [d,E] fp32
+ *   moe_residual_add:  x[t,:] += y[t,:]                                in place
+ */
+int moe_rmsnorm(const float* x, int T, int d, float eps, float* h, void* stream);
+int moe_router_logits(const float* h, const float* w_gate, int T, int d, int E, float* logits,
+                      void* stream);
+int moe_residual_add(float* x, const float* y, int T, int d, void* stream);
+
+/*
+ * Measurement hook: when `hip_event` (a hipEvent_t as void*, HOST handle) is
+ * non-NULL, every following moe_expert_ffn call records it on its stream
+ * between the first projection (x.w1, x.w3, silu*mul) and the second (h.w2),
+ * so a caller bracketing the call with its own events can time the two kernels
+ * separately.  NULL switches the hook off.  Process-wide, not thread-safe.
+ */
+int moe_set_ffn_mid_event(void* hip_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

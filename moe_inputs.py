@@ -9,7 +9,9 @@ Recipe (every array is a pure function of (seed, stream id, shape)):
   * generator: numpy ``Generator(Philox(key=[seed, stream]))`` ->
     ``standard_normal(float32)``, scaled by the stated std;
   * stream ids: 0 = activations x, 1 = router matrix W_g, 2 = router noise z
-    (Zipf-biased workloads), 10+3e+{0,1,2} = w1, w3, w2 of expert e;
+    (Zipf-biased workloads), 10+3e+{0,1,2} = w1, w3, w2 of expert e (drawn
+    from the config's weight seed, which the Mixtral-shaped single-layer
+    workloads share so that one set of matrices serves all three);
   * ``N(0, 1/fan_in)``: std d^-1/2 for W_g, w1, w3 and f^-1/2 for w2;
   * bf16 = round-to-nearest-even of the fp32 draw, stored as uint16;
   * router logits are either fp32(x . W_g) accumulated in fp64 on the host
@@ -46,17 +48,25 @@ class MoEConfig:
     x_dtype: str  # F32 or BF16
     seed: int
     zipf_s: Optional[float] = None  # None: logits = x.W_g ; else z + ln(zipf pmf)
+    w_seed: Optional[int] = None    # seed of the expert matrices (default: seed)
 
     @property
     def N(self) -> int:
         return self.T * self.k
 
+    @property
+    def weight_seed(self) -> int:
+        return self.seed if self.w_seed is None else self.w_seed
+
 
 CONFIGS = {
     "tiny_fp32": MoEConfig("tiny_fp32", 16, 256, 512, 8, 2, F32, F32, 1001),
     "decode_t1": MoEConfig("decode_t1", 1, 4096, 14336, 8, 2, BF16, F32, 1002),
-    "beam_t16": MoEConfig("beam_t16", 16, 4096, 14336, 8, 2, BF16, F32, 1003, 1.2),
-    "prefill_t4096": MoEConfig("prefill_t4096", 4096, 4096, 14336, 8, 2, BF16, BF16, 1004, 1.2),
+    # the three Mixtral-shaped single-layer workloads share one set of expert
+    # matrices (weight seed 1002); activations and logits have their own seeds
+    "beam_t16": MoEConfig("beam_t16", 16, 4096, 14336, 8, 2, BF16, F32, 1003, 1.2, 1002),
+    "prefill_t4096": MoEConfig("prefill_t4096", 4096, 4096, 14336, 8, 2, BF16, BF16, 1004, 1.2,
+                               1002),
 }
 
 
@@ -110,7 +120,7 @@ def expert_matrix(cfg: MoEConfig, e: int, which: int) -> np.ndarray:
         shape, std = (cfg.f, cfg.d), cfg.f ** -0.5
     else:
         shape, std = (cfg.d, cfg.f), cfg.d ** -0.5
-    a = normal_f32(cfg.seed, 10 + 3 * e + which, shape, std)
+    a = normal_f32(cfg.weight_seed, 10 + 3 * e + which, shape, std)
     return f32_to_bf16_bits(a) if cfg.w_dtype == BF16 else a
 
 

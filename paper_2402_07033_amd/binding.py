@@ -1,0 +1,263 @@
+"""ctypes binding of include/moe.h.  Argument marshalling only: tensors become
+device pointers, outputs are allocated with torch when the caller passes none,
+and a non-zero status raises MoeError.  Same names as the C entry points."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_FFN_AUTO, MOE_FFN_STREAM, MOE_FFN_GROUPED = 0, 1, 2
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libmoe_hip.so")
+_lib = None
+
+EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
+           "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
+           "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
+           "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event")
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {moe_status_string(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2402_07033_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(_LIB_PATH)
+        L.moe_status_string.restype = C.c_char_p
+        L.moe_status_string.argtypes = [C.c_int]
+        L.moe_weights_bytes.restype = C.c_size_t
+        L.moe_weights_bytes.argtypes = [C.c_void_p]
+        L.moe_expert_ffn_workspace.restype = C.c_size_t
+        L.moe_expert_ffn_workspace.argtypes = [C.c_int] * 5
+        vp, i32, f32 = C.c_void_p, C.c_int, C.c_float
+        L.moe_route.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        L.moe_permute.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.moe_weights_pack.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.POINTER(vp), vp]
+        L.moe_weights_free.argtypes = [vp]
+        L.moe_expert_ffn.argtypes = [vp, vp, i32, vp, i32, vp, C.c_size_t, vp, vp]
+        L.moe_expert_ffn_path.argtypes = [vp, vp, i32, vp, i32, vp, C.c_size_t, vp, i32, vp]
+        L.moe_combine.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+        L.moe_rmsnorm.argtypes = [vp, i32, i32, f32, vp, vp]
+        L.moe_router_logits.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        L.moe_residual_add.argtypes = [vp, vp, i32, i32, vp]
+        L.moe_set_ffn_mid_event.argtypes = [vp]
+        L.moe_set_ffn_mid_event.restype = C.c_int
+        for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
+                  "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
+                  "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event"):
+            getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def moe_status_string(status: int) -> str:
+    return lib().moe_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise MoeError(status, what)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, what: str):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError(f"{what}: expected a contiguous device tensor of {dtype}")
+    return t
+
+
+def _act_dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MOE_F32
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def moe_route(logits: torch.Tensor, k: int, idx=None, weights=None, stream=None):
+    """logits fp32 [T,E] -> (idx int32 [T,k], weights fp32 [T,k])."""
+    _dev(logits, torch.float32, "logits")
+    T, E = logits.shape
+    if idx is None:
+        idx = torch.empty((T, k), dtype=torch.int32, device=logits.device)
+    if weights is None:
+        weights = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    _check(lib().moe_route(_ptr(logits), T, E, k, _ptr(idx), _ptr(weights), _stream(stream)),
+           "moe_route")
+    return idx, weights
+
+
+def moe_permute(idx: torch.Tensor, E: int, x: Optional[torch.Tensor] = None, out=None,
+                stream=None):
+    """idx int32 [T,k], x [T,d] -> (counts[E], offsets[E+1], perm[N], inv_perm[N], xg[N,d]).
+    `out` may carry preallocated tensors in that order."""
+    _dev(idx, torch.int32, "idx")
+    T, k = idx.shape
+    N = T * k
+    dev = idx.device
+    if out is None:
+        i32 = dict(dtype=torch.int32, device=dev)
+        out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
+               torch.empty(N, **i32),
+               None if x is None else torch.empty((N, x.shape[1]), dtype=x.dtype, device=dev))
+    counts, offsets, perm, inv_perm, xg = out
+    d, xdt = 0, MOE_F32
+    if x is not None:
+        if not x.is_cuda or not x.is_contiguous():
+            raise TypeError("x: expected a contiguous device tensor")
+        d, xdt = x.shape[1], _act_dtype(x)
+    _check(lib().moe_permute(_ptr(idx), T, E, k, _ptr(x), d, xdt, _ptr(counts), _ptr(offsets),
+                             _ptr(perm), _ptr(inv_perm), _ptr(xg), _stream(stream)),
+           "moe_permute")
+    return counts, offsets, perm, inv_perm, xg
+
+
+class PackedWeights:
+    """Owner of a moe_weights_t handle."""
+
+    def __init__(self, handle: int, E: int, d: int, f: int, dtype: int):
+        self.handle, self.E, self.d, self.f, self.dtype = handle, E, d, f, dtype
+
+    @property
+    def nbytes(self) -> int:
+        return int(lib().moe_weights_bytes(C.c_void_p(self.handle))) if self.handle else 0
+
+    def free(self):
+        if self.handle:
+            h, self.handle = self.handle, 0
+            _check(lib().moe_weights_free(C.c_void_p(h)), "moe_weights_free")
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def moe_weights_pack(w1: torch.Tensor, w3: torch.Tensor, w2: torch.Tensor,
+                     stream=None) -> PackedWeights:
+    """w1, w3 [E,d,f], w2 [E,f,d], all fp32 or all bf16 device tensors."""
+    dt = _act_dtype(w1)
+    for t, n in ((w1, "w1"), (w3, "w3"), (w2, "w2")):
+        _dev(t, w1.dtype, n)
+    E, d, f = w1.shape
+    if tuple(w3.shape) != (E, d, f) or tuple(w2.shape) != (E, f, d):
+        raise ValueError("weight shapes must be w1,w3 [E,d,f] and w2 [E,f,d]")
+    h = C.c_void_p()
+    _check(lib().moe_weights_pack(_ptr(w1), _ptr(w3), _ptr(w2), E, d, f, dt, C.byref(h),
+                                  _stream(stream)), "moe_weights_pack")
+    return PackedWeights(h.value, E, d, f, dt)
+
+
+def moe_weights_free(w: PackedWeights):
+    w.free()
+
+
+def moe_expert_ffn_workspace(N: int, E: int, d: int, f: int, act_dtype: int = MOE_F32) -> int:
+    return int(lib().moe_expert_ffn_workspace(N, E, d, f, act_dtype))
+
+
+def moe_expert_ffn(W: PackedWeights, xg: torch.Tensor, offsets: torch.Tensor, workspace=None,
+                   yg=None, path: int = MOE_FFN_AUTO, stream=None):
+    """xg [N,d] (fp32 or bf16), offsets int32 [E+1] on the device -> yg fp32 [N,d]."""
+    _dev(offsets, torch.int32, "offsets")
+    if not xg.is_cuda or not xg.is_contiguous():
+        raise TypeError("xg: expected a contiguous device tensor")
+    N = xg.shape[0]
+    adt = _act_dtype(xg)
+    if workspace is None:
+        need = moe_expert_ffn_workspace(N, W.E, W.d, W.f, adt)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=xg.device)
+    if yg is None:
+        yg = torch.empty((N, W.d), dtype=torch.float32, device=xg.device)
+    _check(lib().moe_expert_ffn_path(C.c_void_p(W.handle), _ptr(xg), adt, _ptr(offsets), N,
+                                     _ptr(workspace), workspace.numel(), _ptr(yg), path,
+                                     _stream(stream)), "moe_expert_ffn")
+    return yg
+
+
+def moe_combine(yg: torch.Tensor, inv_perm: torch.Tensor, weights: torch.Tensor, y=None,
+                stream=None):
+    """yg fp32 [N,d], inv_perm int32 [N], weights fp32 [T,k] -> y fp32 [T,d]."""
+    _dev(yg, torch.float32, "yg")
+    _dev(inv_perm, torch.int32, "inv_perm")
+    _dev(weights, torch.float32, "weights")
+    T, k = weights.shape
+    d = yg.shape[1]
+    if y is None:
+        y = torch.empty((T, d), dtype=torch.float32, device=yg.device)
+    _check(lib().moe_combine(_ptr(yg), _ptr(inv_perm), _ptr(weights), T, k, d, _ptr(y),
+                             _stream(stream)), "moe_combine")
+    return y
+
+
+def moe_rmsnorm(x: torch.Tensor, eps: float = 1e-5, h=None, stream=None):
+    _dev(x, torch.float32, "x")
+    if h is None:
+        h = torch.empty_like(x)
+    _check(lib().moe_rmsnorm(_ptr(x), x.shape[0], x.shape[1], eps, _ptr(h), _stream(stream)),
+           "moe_rmsnorm")
+    return h
+
+
+def moe_router_logits(h: torch.Tensor, w_gate: torch.Tensor, logits=None, stream=None):
+    _dev(h, torch.float32, "h")
+    _dev(w_gate, torch.float32, "w_gate")
+    T, d = h.shape
+    E = w_gate.shape[1]
+    if logits is None:
+        logits = torch.empty((T, E), dtype=torch.float32, device=h.device)
+    _check(lib().moe_router_logits(_ptr(h), _ptr(w_gate), T, d, E, _ptr(logits),
+                                   _stream(stream)), "moe_router_logits")
+    return logits
+
+
+def moe_residual_add(x: torch.Tensor, y: torch.Tensor, stream=None):
+    _dev(x, torch.float32, "x")
+    _dev(y, torch.float32, "y")
+    _check(lib().moe_residual_add(_ptr(x), _ptr(y), x.shape[0], x.shape[1], _stream(stream)),
+           "moe_residual_add")
+    return x
+
+
+def moe_set_ffn_mid_event(hip_event: Optional[int]):
+    """hipEvent_t handle (int) recorded between the two projections, or None."""
+    _check(lib().moe_set_ffn_mid_event(C.c_void_p(hip_event) if hip_event else None),
+           "moe_set_ffn_mid_event")
+
+
+def moe_layer(W: PackedWeights, x: torch.Tensor, logits: torch.Tensor, k: int,
+              path: int = MOE_FFN_AUTO, workspace=None, stream=None) -> dict:
+    """The four calls of the hot path in order; returns every intermediate."""
+    idx, w = moe_route(logits, k, stream=stream)
+    counts, offsets, perm, inv_perm, xg = moe_permute(idx, W.E, x, stream=stream)
+    yg = moe_expert_ffn(W, xg, offsets, workspace=workspace, path=path, stream=stream)
+    y = moe_combine(yg, inv_perm, w, stream=stream)
+    return dict(idx=idx, w=w, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm,
+                xg=xg, yg=yg, y=y)

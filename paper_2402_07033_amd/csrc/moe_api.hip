@@ -1,0 +1,155 @@
+// C ABI of libmoe_hip (include/moe.h): argument validation on the host, then
+// dispatch to the kernel launchers.  Nothing is enqueued when validation fails.
+#include "moe_internal.h"
+
+static inline bool dims_ok(int d) { return d >= 64 && d % 64 == 0 && d <= (1 << 20); }
+static inline bool tek_ok(int T, int E, int k) {
+    return T >= 0 && E >= 1 && E <= MOE_MAX_E && k >= 1 && k <= MOE_MAX_K && k <= E &&
+           (long long)T * k < MOE_MAX_N;
+}
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+hipEvent_t g_moe_mid_event = nullptr;
+
+extern "C" {
+
+int moe_set_ffn_mid_event(void* hip_event) {
+    g_moe_mid_event = (hipEvent_t)hip_event;
+    return MOE_OK;
+}
+
+const char* moe_status_string(int status) {
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case MOE_ERR_WORKSPACE: return "workspace missing or too small";
+        case MOE_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int moe_route(const float* logits, int T, int E, int k, int32_t* idx, float* weights,
+              void* stream) {
+    if (!tek_ok(T, E, k)) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!logits || !idx || !weights) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(logits) || !moe_aligned16(idx) || !moe_aligned16(weights))
+        return MOE_ERR_INVALID_ARG;
+    return moe_route_launch(logits, T, E, k, idx, weights, (hipStream_t)stream);
+}
+
+int moe_permute(const int32_t* idx, int T, int E, int k, const void* x, int d,
+                moe_dtype_t x_dtype, int32_t* counts, int32_t* offsets, int32_t* perm,
+                int32_t* inv_perm, void* xg, void* stream) {
+    if (!tek_ok(T, E, k)) return MOE_ERR_INVALID_ARG;
+    if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
+    if (T > 0 && (!idx || !perm || !inv_perm)) return MOE_ERR_INVALID_ARG;
+    if ((x == nullptr) != (xg == nullptr)) return MOE_ERR_INVALID_ARG;
+    if (x) {
+        if (!dims_ok(d) || (x_dtype != MOE_F32 && x_dtype != MOE_BF16)) return MOE_ERR_INVALID_ARG;
+        if (!moe_aligned16(x) || !moe_aligned16(xg)) return MOE_ERR_INVALID_ARG;
+    }
+    if (!moe_aligned16(idx) || !moe_aligned16(perm) || !moe_aligned16(inv_perm))
+        return MOE_ERR_INVALID_ARG;
+    // T == 0 still writes counts = 0 and offsets = 0.
+    return moe_permute_launch(idx, T, E, k, T > 0 ? x : nullptr, d, x_dtype, counts, offsets, perm,
+                              inv_perm, xg, (hipStream_t)stream);
+}
+
+int moe_weights_pack(const void* w1, const void* w3, const void* w2, int E, int d, int f,
+                     moe_dtype_t w_dtype, moe_weights_t** out, void* stream) {
+    if (!out) return MOE_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!w1 || !w3 || !w2 || E < 1 || E > MOE_MAX_E || !dims_ok(d) || !dims_ok(f))
+        return MOE_ERR_INVALID_ARG;
+    if (w_dtype != MOE_F32 && w_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(w1) || !moe_aligned16(w3) || !moe_aligned16(w2)) return MOE_ERR_INVALID_ARG;
+    return moe_weights_pack_impl(w1, w3, w2, E, d, f, w_dtype, out, (hipStream_t)stream);
+}
+
+int moe_weights_free(moe_weights_t* w) { return moe_weights_free_impl(w); }
+
+size_t moe_weights_bytes(const moe_weights_t* w) { return w ? w->bytes : 0; }
+
+size_t moe_expert_ffn_workspace(int N, int E, int d, int f, moe_dtype_t act_dtype) {
+    if (N < 0 || N >= MOE_MAX_N || E < 1 || E > MOE_MAX_E || !dims_ok(d) || !dims_ok(f)) return 0;
+    if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return 0;
+    size_t need = moe_ffn_f32_workspace(N, E, d, f);
+    const size_t s = moe_ffn_stream_workspace(N, E, d, f);
+    const size_t g = moe_ffn_grouped_workspace(N, E, d, f);
+    if (s > need) need = s;
+    if (g > need) need = g;
+    return align256(need) + 256;
+}
+
+int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                        const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
+                        float* yg, int path, void* stream) {
+    if (!W || N < 0 || N >= MOE_MAX_N) return MOE_ERR_INVALID_ARG;
+    if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (path != MOE_FFN_AUTO && path != MOE_FFN_STREAM && path != MOE_FFN_GROUPED)
+        return MOE_ERR_INVALID_ARG;
+    if (!offsets) return MOE_ERR_INVALID_ARG;
+    if (N == 0) return MOE_OK;
+    if (!xg || !yg || !moe_aligned16(xg) || !moe_aligned16(yg)) return MOE_ERR_INVALID_ARG;
+    if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
+    if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, act_dtype))
+        return MOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (W->dtype == MOE_F32) {
+        if (act_dtype != MOE_F32 || path != MOE_FFN_AUTO) return MOE_ERR_UNSUPPORTED;
+        return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
+    }
+    if (path == MOE_FFN_AUTO) {
+        // Up to 32 routed rows (16 tokens, top-2) no expert has more than one
+        // 16-row tile and the layer is weight-bandwidth bound: stream.
+        path = (N <= 32 && moe_ffn_stream_supported(W->d, W->f)) ? MOE_FFN_STREAM
+                                                                   : MOE_FFN_GROUPED;
+    }
+    if (path == MOE_FFN_STREAM)
+        return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
+    return moe_ffn_grouped_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
+}
+
+int moe_expert_ffn(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                   const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
+                   float* yg, void* stream) {
+    return moe_expert_ffn_path(W, xg, act_dtype, offsets, N, workspace, workspace_bytes, yg,
+                               MOE_FFN_AUTO, stream);
+}
+
+int moe_combine(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
+                int d, float* y, void* stream) {
+    if (T < 0 || k < 1 || k > MOE_MAX_K || (long long)T * k >= MOE_MAX_N || !dims_ok(d))
+        return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!yg || !inv_perm || !weights || !y) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(yg) || !moe_aligned16(y)) return MOE_ERR_INVALID_ARG;
+    return moe_combine_launch(yg, inv_perm, weights, T, k, d, y, (hipStream_t)stream);
+}
+
+int moe_rmsnorm(const float* x, int T, int d, float eps, float* h, void* stream) {
+    if (T < 0 || !dims_ok(d) || !(eps >= 0.f)) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !h) return MOE_ERR_INVALID_ARG;
+    return moe_rmsnorm_launch(x, T, d, eps, h, (hipStream_t)stream);
+}
+
+int moe_router_logits(const float* h, const float* w_gate, int T, int d, int E, float* logits,
+                      void* stream) {
+    if (T < 0 || !dims_ok(d) || E < 1 || E > MOE_MAX_E) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!h || !w_gate || !logits) return MOE_ERR_INVALID_ARG;
+    return moe_router_logits_launch(h, w_gate, T, d, E, logits, (hipStream_t)stream);
+}
+
+int moe_residual_add(float* x, const float* y, int T, int d, void* stream) {
+    if (T < 0 || !dims_ok(d)) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !y || !moe_aligned16(x) || !moe_aligned16(y)) return MOE_ERR_INVALID_ARG;
+    return moe_residual_add_launch(x, y, T, d, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,298 @@
+// Decode-sized expert FFN for gfx950: weight-streaming kernels on the bf16
+// matrix cores.
+//
+// With a handful of rows per expert the layer is bound by the time to read
+// each active expert's matrices once (the paper's observation that GPU expert
+// latency is set by parameter loading, Sec. 3.1 / Appendix A).  The kernels
+// therefore stream every fragment of an active expert exactly once, with
+// 16-byte-per-lane fully coalesced loads kept 16 deep per wavefront, and do the
+// arithmetic with v_mfma_f32_16x16x32_bf16: the weight fragment is the A
+// operand (16 output features x 32 reduction indices), up to 16 token rows of
+// the expert form the B operand, fp32 accumulate.  fp32 activations are split
+// into bf16 high and low parts and multiplied separately, which keeps them to
+// ~2^-16 relative; the matrix cores are otherwise idle here.
+//
+// Work decomposition (both projections): a unit is (row tile of <=16 rows of
+// one expert, reduction part, block of 16 output features).  The W waves of a
+// workgroup split the unit's reduction range; their partial 16x16 tiles meet
+// in LDS.  Each wave keeps its slice of the activations in registers across
+// all consecutive units of the same (tile, part), so activations are read once
+// per workgroup, and the units are dealt to the workgroups in contiguous,
+// equal ranges so that every workgroup streams the same number of bytes.
+//   up   (x.w1, x.w3 -> silu*mul -> h): one part (the nonlinearity needs the
+//        full sum), 8 waves x d/256 reduction steps.
+//   down (h.w2 -> yg): the long reduction over f is cut into P parts that are
+//        summed into yg with fp32 atomics (yg is zeroed by the up kernel).
+#include "moe_internal.h"
+
+#define ST_MAX_TILES 128
+#define ST_MAX_WAVES 8
+
+struct StreamArgs {
+    const u32x4_t* wfrag;  // fragment-ordered weights
+    const void* act;       // [N,K] fp32 or bf16
+    const int32_t* offsets;
+    float* out;       // up: h [N,C]; down: yg [N,C]
+    float* zero_ptr;  // buffer zero-filled by this launch (or null)
+    size_t zero_n4;   // its size in float4
+    int E, N, K, C;
+    int NB;  // C / 16
+    int KS;  // K / 32
+    int P;   // reduction parts per unit row
+    int W;   // waves per workgroup
+};
+
+template <int KSW, bool ACT_BF16>
+__device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 1 : 2],
+                                                const void* actp, int K, int row0, int rows,
+                                                int ks0, int lane) {
+    const int t = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < KSW; s++) {
+        const size_t off = (size_t)(row0 + t) * K + (size_t)(ks0 + s) * 32 + kq * 8;
+        if (ACT_BF16) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (t < rows) v = *(const u32x4_t*)((const uint16_t*)actp + off);
+            act[s][0] = __builtin_bit_cast(bf16x8_t, v);
+        } else {
+            float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (t < rows) {
+                const float4 v0 = *(const float4*)((const float*)actp + off);
+                const float4 v1 = *(const float4*)((const float*)actp + off + 4);
+                x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+                x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
+            }
+            unsigned hi[8], lo[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                hi[j] = moe_bf16_rne(x[j]);
+                lo[j] = moe_bf16_rne(x[j] - moe_bf16_to_f32(hi[j]));
+            }
+            u32x4_t vh = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),
+                          hi[6] | (hi[7] << 16)};
+            u32x4_t vl = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),
+                          lo[6] | (lo[7] << 16)};
+            act[s][0] = __builtin_bit_cast(bf16x8_t, vh);
+            act[s][ACT_BF16 ? 0 : 1] = __builtin_bit_cast(bf16x8_t, vl);
+        }
+    }
+}
+
+template <int KSW, int NMAT, bool ACT_BF16>
+__global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
+    constexpr int TERMS = ACT_BF16 ? 1 : 2;
+    constexpr int NL = KSW * NMAT;         // fragment loads per unit per wave
+    constexpr int R = NL < 16 ? NL : 16;   // loads kept in flight per wave
+    __shared__ int s_te[ST_MAX_TILES], s_tr0[ST_MAX_TILES], s_trn[ST_MAX_TILES];
+    __shared__ int s_nt;
+    __shared__ f32x4_t s_red[2][ST_MAX_WAVES][NMAT][64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    if (a.zero_ptr) {
+        float4* z = (float4*)a.zero_ptr;
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + tid; i < a.zero_n4;
+             i += (size_t)gridDim.x * blockDim.x)
+            z[i] = zero;
+    }
+    if (tid == 0) {
+        int n = 0;
+        for (int e = 0; e < a.E; e++) {
+            int lo = a.offsets[e], hi = a.offsets[e + 1];
+            lo = lo < 0 ? 0 : (lo > a.N ? a.N : lo);
+            hi = hi < lo ? lo : (hi > a.N ? a.N : hi);
+            for (int r = lo; r < hi && n < ST_MAX_TILES; r += 16) {
+                s_te[n] = e;
+                s_tr0[n] = r;
+                s_trn[n] = (hi - r) < 16 ? (hi - r) : 16;
+                n++;
+            }
+        }
+        s_nt = n;
+    }
+    __syncthreads();
+    const long long total = (long long)s_nt * a.P * a.NB;
+    const long long u_begin = total * blockIdx.x / gridDim.x;
+    const long long u_end = total * (blockIdx.x + 1) / gridDim.x;
+    if (u_begin >= u_end) return;  // uniform over the workgroup
+
+    const int wave_ks = wave * KSW;  // this wave's first reduction step inside a part
+    const int part_ks = a.W * KSW;   // reduction steps per part
+    // fragment index of load 0 of unit u for this wave
+    auto frag_base = [&](long long u, int& tile, int& part, int& nb) -> size_t {
+        nb = (int)(u % a.NB);
+        const long long tp = u / a.NB;
+        part = (int)(tp % a.P);
+        tile = (int)(tp / a.P);
+        const int e = s_te[tile];
+        return (((size_t)e * a.NB + nb) * NMAT) * a.KS + (size_t)part * part_ks + wave_ks;
+    };
+    auto ld = [&](size_t fb, int i) -> u32x4_t {
+        const int mat = i / KSW, s = i % KSW;
+        return __builtin_nontemporal_load(a.wfrag + ((fb + (size_t)mat * a.KS + s) * 64 + lane));
+    };
+
+    int tile, part, nb;
+    size_t fb = frag_base(u_begin, tile, part, nb);
+    u32x4_t buf[R];
+#pragma unroll
+    for (int i = 0; i < R; i++) buf[i] = ld(fb, i);
+
+    bf16x8_t act[KSW][TERMS];
+    int cur_tile = -1, cur_part = -1;
+    int it = 0;
+    for (long long u = u_begin; u < u_end; ++u, ++it) {
+        const int row0 = s_tr0[tile], rows = s_trn[tile];
+        if (tile != cur_tile || part != cur_part) {
+            stream_load_act<KSW, ACT_BF16>(act, a.act, a.K, row0, rows, part * part_ks + wave_ks,
+                                           lane);
+            cur_tile = tile;
+            cur_part = part;
+        }
+        const bool has_next = (u + 1 < u_end);
+        int ntile = tile, npart = part, nnb = nb;
+        size_t fb_next = fb;
+        if (has_next) fb_next = frag_base(u + 1, ntile, npart, nnb);
+
+        f32x4_t acc[NMAT][TERMS];
+#pragma unroll
+        for (int m = 0; m < NMAT; m++)
+#pragma unroll
+            for (int t = 0; t < TERMS; t++) acc[m][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < NL; i++) {
+            const int mat = i / KSW, s = i % KSW;
+            const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, buf[i % R]);
+#pragma unroll
+            for (int t = 0; t < TERMS; t++)
+                acc[mat][t] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, act[s][t], acc[mat][t], 0, 0, 0);
+            const int j = i + R;
+            if (j < NL) {
+                buf[i % R] = ld(fb, j);
+            } else if (has_next) {
+                buf[i % R] = ld(fb_next, j - NL);
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < NMAT; m++) {
+            f32x4_t v = acc[m][0];
+            if (TERMS == 2) v += acc[m][TERMS - 1];
+            s_red[it & 1][wave][m][lane] = v;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+            for (int w = 0; w < a.W; w++) {
+                sa += s_red[it & 1][w][0][lane];
+                if (NMAT == 2) sb += s_red[it & 1][w][NMAT - 1][lane];
+            }
+            const int t = lane & 15;
+            if (t < rows) {
+                float* dst = a.out + (size_t)(row0 + t) * a.C + nb * 16 + 4 * (lane >> 4);
+                if (NMAT == 2) {
+                    float4 h;
+                    h.x = sa[0] / (1.0f + __expf(-sa[0])) * sb[0];
+                    h.y = sa[1] / (1.0f + __expf(-sa[1])) * sb[1];
+                    h.z = sa[2] / (1.0f + __expf(-sa[2])) * sb[2];
+                    h.w = sa[3] / (1.0f + __expf(-sa[3])) * sb[3];
+                    *(float4*)dst = h;
+                } else if (a.P == 1) {
+                    *(float4*)dst = make_float4(sa[0], sa[1], sa[2], sa[3]);
+                } else {
+                    unsafeAtomicAdd(dst + 0, sa[0]);
+                    unsafeAtomicAdd(dst + 1, sa[1]);
+                    unsafeAtomicAdd(dst + 2, sa[2]);
+                    unsafeAtomicAdd(dst + 3, sa[3]);
+                }
+            }
+        }
+        fb = fb_next;
+        tile = ntile;
+        part = npart;
+        nb = nnb;
+    }
+}
+
+// Split a reduction of KS steps (of 32) into P parts x W waves x KSW steps.
+static bool stream_pick(int KS, bool allow_parts, int& W, int& KSW, int& P) {
+    int best = -1;
+    const int ksws[5] = {16, 8, 4, 2, 1};
+    for (int i = 0; i < 5; i++)
+        for (int w = ST_MAX_WAVES; w >= 1; w--) {
+            const int span = w * ksws[i];
+            if (KS % span) continue;
+            const int p = KS / span;
+            if (!allow_parts && p != 1) continue;
+            const int score = span * 16 + w;
+            if (score > best) {
+                best = score;
+                W = w;
+                KSW = ksws[i];
+                P = p;
+            }
+        }
+    return best >= 0;
+}
+
+bool moe_ffn_stream_supported(int d, int f) {
+    int W, KSW, P;
+    return stream_pick(d / 32, false, W, KSW, P) && stream_pick(f / 32, true, W, KSW, P);
+}
+
+size_t moe_ffn_stream_workspace(int N, int E, int d, int f) {
+    (void)E;
+    (void)d;
+    return (size_t)N * f * sizeof(float);
+}
+
+template <int NMAT, bool ACT_BF16>
+static int stream_dispatch(int KSW, dim3 grid, dim3 block, hipStream_t s, const StreamArgs& a) {
+    switch (KSW) {
+        case 1: hipLaunchKernelGGL((stream_kernel<1, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
+        case 2: hipLaunchKernelGGL((stream_kernel<2, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
+        case 4: hipLaunchKernelGGL((stream_kernel<4, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
+        case 8: hipLaunchKernelGGL((stream_kernel<8, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
+        case 16: hipLaunchKernelGGL((stream_kernel<16, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
+        default: return MOE_ERR_UNSUPPORTED;
+    }
+    return moe_launch_status();
+}
+
+int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
+                          const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
+    const int d = W->d, f = W->f, E = W->E;
+    if (N / 16 + E > ST_MAX_TILES) return MOE_ERR_UNSUPPORTED;
+    int Wu, KSWu, Pu, Wd, KSWd, Pd;
+    if (!stream_pick(d / 32, false, Wu, KSWu, Pu) || !stream_pick(f / 32, true, Wd, KSWd, Pd))
+        return MOE_ERR_UNSUPPORTED;
+    float* h = (float*)ws;
+    const unsigned grid = (unsigned)moe_num_cus();
+
+    StreamArgs up;
+    up.wfrag = (const u32x4_t*)W->w13;
+    up.act = xg;
+    up.offsets = offsets;
+    up.out = h;
+    up.zero_ptr = (Pd > 1) ? yg : nullptr;
+    up.zero_n4 = (size_t)N * d / 4;
+    up.E = E; up.N = N; up.K = d; up.C = f;
+    up.NB = f / 16; up.KS = d / 32; up.P = 1; up.W = Wu;
+    int rc = (act_dtype == MOE_BF16)
+                 ? stream_dispatch<2, true>(KSWu, dim3(grid), dim3(64 * Wu), s, up)
+                 : stream_dispatch<2, false>(KSWu, dim3(grid), dim3(64 * Wu), s, up);
+    if (rc != MOE_OK) return rc;
+    moe_record_mid_event(s);
+
+    StreamArgs dn;
+    dn.wfrag = (const u32x4_t*)W->w2;
+    dn.act = h;
+    dn.offsets = offsets;
+    dn.out = yg;
+    dn.zero_ptr = nullptr;
+    dn.zero_n4 = 0;
+    dn.E = E; dn.N = N; dn.K = f; dn.C = d;
+    dn.NB = d / 16; dn.KS = f / 32; dn.P = Pd; dn.W = Wd;
+    return stream_dispatch<1, false>(KSWd, dim3(grid), dim3(64 * Wd), s, dn);
+}

@@ -1,0 +1,109 @@
+// Internal declarations shared by the translation units of libmoe_hip.
+// Nothing here is part of the C ABI (see include/moe.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+#define MOE_MAX_E 64
+#define MOE_MAX_K 8
+#define MOE_MAX_N (1 << 24)
+
+// bf16 weights are stored in "fragment order": the unit is the operand tile of
+// one v_mfma_f32_16x16x32_bf16 -- 16 output features (rows of W^T) by 32
+// reduction indices -- laid out exactly as the 64 lanes hold it: lane l owns
+// feature (l % 16) and the 8 consecutive reduction indices 8*(l / 16) .. +7,
+// as one 16-byte chunk at byte offset 16*l.  A fragment is 1 KiB, so a
+// wavefront fetches it with one fully coalesced 16-byte-per-lane load.
+//   w13 : [E][f/16][2 (w1,w3)][d/32] fragments   (reduction over d)
+//   w2  : [E][d/16][f/32]           fragments   (reduction over f)
+#define MOE_FRAG_BYTES 1024
+#define MOE_FRAG_ELEMS 512
+
+struct moe_weights {
+    int E, d, f;
+    moe_dtype_t dtype;
+    int device;
+    // bf16: fragment-ordered w13 and w2.  fp32: w1f/w3f/w2f plain copies.
+    void* w13;
+    void* w2;
+    float* w1f;
+    float* w3f;
+    float* w2f;
+    size_t bytes;
+};
+
+static inline bool moe_aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+#define MOE_HIP_TRY(expr)                       \
+    do {                                        \
+        if ((expr) != hipSuccess) {             \
+            (void)hipGetLastError();            \
+            return MOE_ERR_HIP;                 \
+        }                                       \
+    } while (0)
+
+static inline int moe_launch_status() {
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// Event recorded between the two projections of moe_expert_ffn (measurement hook), or null.
+extern hipEvent_t g_moe_mid_event;
+static inline void moe_record_mid_event(hipStream_t s) {
+    if (g_moe_mid_event) (void)hipEventRecord(g_moe_mid_event, s);
+}
+
+// Number of compute units of the current device (cached per process; 256 on MI355X).
+int moe_num_cus();
+
+// ---- expert FFN kernel families (each returns a moe_status_t) ----------------
+size_t moe_ffn_f32_workspace(int N, int E, int d, int f);
+int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* offsets, int N,
+                       void* ws, float* yg, hipStream_t s);
+
+bool moe_ffn_stream_supported(int d, int f);
+size_t moe_ffn_stream_workspace(int N, int E, int d, int f);
+int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
+                          const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
+
+size_t moe_ffn_grouped_workspace(int N, int E, int d, int f);
+int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
+                           const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
+
+// ---- small device helpers ------------------------------------------------------
+#ifdef __HIPCC__
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ unsigned moe_bf16_rne(float v) {
+    unsigned u = __float_as_uint(v);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float moe_bf16_to_f32(unsigned bits) {
+    return __uint_as_float(bits << 16);
+}
+__device__ __forceinline__ unsigned moe_pack_bf16x2(float lo, float hi) {
+    return moe_bf16_rne(lo) | (moe_bf16_rne(hi) << 16);
+}
+#endif
+
+// ---- launchers of the small kernels (moe_route_permute.hip, moe_weights.hip) ----
+int moe_route_launch(const float* logits, int T, int E, int k, int32_t* idx, float* weights,
+                     hipStream_t s);
+int moe_permute_launch(const int32_t* idx, int T, int E, int k, const void* x, int d,
+                       moe_dtype_t x_dtype, int32_t* counts, int32_t* offsets, int32_t* perm,
+                       int32_t* inv_perm, void* xg, hipStream_t s);
+int moe_combine_launch(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
+                       int d, float* y, hipStream_t s);
+int moe_rmsnorm_launch(const float* x, int T, int d, float eps, float* h, hipStream_t s);
+int moe_router_logits_launch(const float* h, const float* w_gate, int T, int d, int E,
+                             float* logits, hipStream_t s);
+int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t s);
+int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E, int d, int f,
+                          moe_dtype_t w_dtype, moe_weights** out, hipStream_t s);
+int moe_weights_free_impl(moe_weights* W);

@@ -1,0 +1,355 @@
+// Gating top-k, per-expert batching and gate-weighted combine for gfx950.
+//
+// route  : G = next power of two >= E lanes of a wavefront hold one token's
+//          logits; k rounds of a butterfly arg-max (value desc, index asc)
+//          pick the experts; the softmax over the k winners is fp32.
+// permute: a stable counting sort of the T*k slots keyed on the expert.  Ranks
+//          come from wavefront ballots (lanes below me with my expert) plus a
+//          scan over the waves of a 1024-slot chunk, so the order inside an
+//          expert segment is the slot order and the result is unique.
+// combine: y[t] = sum_j w[t,j] * yg[inv_perm[t*k+j]], float4 lanes along d.
+#include "moe_internal.h"
+
+// ------------------------------------------------------------------ route ----
+
+template <int G>
+__global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ logits, int T, int E,
+                                                    int k, int32_t* __restrict__ idx,
+                                                    float* __restrict__ weights) {
+    const int tid = blockIdx.x * 256 + threadIdx.x;
+    const int t = tid / G;
+    const int gl = tid % G;  // lane inside the token's group = expert id it holds
+    const bool live = (t < T);
+    float v = -INFINITY;
+    int e = 0x7fffffff;
+    if (live && gl < E) {
+        v = logits[(size_t)t * E + gl];
+        e = gl;
+    }
+    float my_v = 0.f, top_v = 0.f;
+    int my_i = 0;
+    for (int j = 0; j < k; j++) {
+        float bv = v;
+        int be = e;
+#pragma unroll
+        for (int m = 1; m < G; m <<= 1) {
+            float ov = __shfl_xor(bv, m, 64);
+            int oe = __shfl_xor(be, m, 64);
+            if (ov > bv || (ov == bv && oe < be)) {
+                bv = ov;
+                be = oe;
+            }
+        }
+        if (j == 0) top_v = bv;
+        if (gl == j) {
+            my_v = bv;
+            my_i = be;
+        }
+        if (e == be) {  // the winner leaves the contest
+            v = -INFINITY;
+            e = 0x7fffffff;
+        }
+    }
+    float u = (gl < k) ? expf(my_v - top_v) : 0.f;
+    float s = u;
+#pragma unroll
+    for (int m = 1; m < G; m <<= 1) s += __shfl_xor(s, m, 64);
+    if (live && gl < k) {
+        idx[(size_t)t * k + gl] = my_i;
+        weights[(size_t)t * k + gl] = u / s;
+    }
+}
+
+int moe_route_launch(const float* logits, int T, int E, int k, int32_t* idx, float* weights,
+                     hipStream_t s) {
+    int G = 1;
+    while (G < E) G <<= 1;
+    if (G < k) G = 8;  // cannot happen (k <= E); keeps lanes gl < k inside the group
+    const int tok_per_block = 256 / G;
+    const unsigned grid = (unsigned)((T + tok_per_block - 1) / tok_per_block);
+#define ROUTE_CASE(g)                                                                         \
+    case g:                                                                                   \
+        hipLaunchKernelGGL(route_kernel<g>, dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, \
+                           weights);                                                          \
+        break;
+    switch (G) {
+        ROUTE_CASE(1)
+        ROUTE_CASE(2)
+        ROUTE_CASE(4)
+        ROUTE_CASE(8)
+        ROUTE_CASE(16)
+        ROUTE_CASE(32)
+        ROUTE_CASE(64)
+        default:
+            return MOE_ERR_INVALID_ARG;
+    }
+#undef ROUTE_CASE
+    return moe_launch_status();
+}
+
+// ---------------------------------------------------------------- permute ----
+
+#define PERM_THREADS 1024
+#define PERM_WAVES (PERM_THREADS / 64)
+
+// Index part of the permute for all N slots, run by ONE workgroup of 1024
+// threads (every workgroup of a launch runs it redundantly when N <= 1024, so
+// that each can then gather its share of rows without a second launch).
+// Outputs are written only when `write` is set.  Returns through LDS: s_off.
+__device__ void permute_indices(const int32_t* __restrict__ idx, int N, int E,
+                                int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                bool write, int* s_cnt /*[64]*/, int* s_off /*[65]*/,
+                                int* s_wave /*[PERM_WAVES][64]*/, int* s_pos /*[1024] or null*/) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    if (tid < MOE_MAX_E) s_cnt[tid] = 0;
+    __syncthreads();
+    for (int p = tid; p < N; p += PERM_THREADS) {
+        int e = idx[p];
+        e = e < 0 ? 0 : (e >= E ? E - 1 : e);
+        atomicAdd(&s_cnt[e], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; e++) {
+            s_off[e] = run;
+            run += s_cnt[e];
+        }
+        s_off[E] = run;
+    }
+    __syncthreads();
+    if (write) {
+        if (tid < E) counts[tid] = s_cnt[tid];
+        if (tid <= E) offsets[tid] = s_off[tid];
+    }
+    // s_cnt now becomes the running number of slots already placed per expert.
+    __syncthreads();
+    if (tid < MOE_MAX_E) s_cnt[tid] = 0;
+    __syncthreads();
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    for (int base = 0; base < N; base += PERM_THREADS) {
+        const int p = base + tid;
+        int e = -1;
+        if (p < N) {
+            e = idx[p];
+            e = e < 0 ? 0 : (e >= E ? E - 1 : e);
+        }
+        int rank = 0;
+        for (int ee = 0; ee < E; ee++) {
+            unsigned long long m = __ballot(e == ee);
+            if (e == ee) rank = __popcll(m & below);
+            if (lane == 0) s_wave[wave * MOE_MAX_E + ee] = __popcll(m);
+        }
+        __syncthreads();
+        if (tid < E) {
+            int run = s_cnt[tid];
+            for (int w = 0; w < PERM_WAVES; w++) {
+                int c = s_wave[w * MOE_MAX_E + tid];
+                s_wave[w * MOE_MAX_E + tid] = run;
+                run += c;
+            }
+            s_cnt[tid] = run;
+        }
+        __syncthreads();
+        if (p < N) {
+            const int pos = s_off[e] + s_wave[wave * MOE_MAX_E + e] + rank;
+            if (write) {
+                perm[pos] = p;
+                inv_perm[p] = pos;
+            }
+            if (s_pos) s_pos[p] = pos;
+        }
+        __syncthreads();
+    }
+}
+
+// N <= 1024: one launch does everything.  Every workgroup computes the slot
+// positions in LDS, workgroup 0 writes the index outputs, and the workgroups
+// share the row gather (16-byte chunks, coalesced along d).
+__global__ __launch_bounds__(PERM_THREADS) void permute_small_kernel(
+    const int32_t* __restrict__ idx, int N, int E, int k, const uint4* __restrict__ x,
+    int row_chunks /* 16-byte chunks per row */, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+    uint4* __restrict__ xg) {
+    __shared__ int s_cnt[MOE_MAX_E];
+    __shared__ int s_off[MOE_MAX_E + 1];
+    __shared__ int s_wave[PERM_WAVES * MOE_MAX_E];
+    __shared__ int s_pos[PERM_THREADS];
+    permute_indices(idx, N, E, counts, offsets, perm, inv_perm, blockIdx.x == 0, s_cnt, s_off,
+                    s_wave, s_pos);
+    if (x == nullptr) return;
+    __syncthreads();
+    for (int p = blockIdx.x; p < N; p += gridDim.x) {
+        const uint4* src = x + (size_t)(p / k) * row_chunks;
+        uint4* dst = xg + (size_t)s_pos[p] * row_chunks;
+        for (int c = threadIdx.x; c < row_chunks; c += PERM_THREADS) dst[c] = src[c];
+    }
+}
+
+__global__ __launch_bounds__(PERM_THREADS) void permute_index_kernel(
+    const int32_t* __restrict__ idx, int N, int E, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    __shared__ int s_cnt[MOE_MAX_E];
+    __shared__ int s_off[MOE_MAX_E + 1];
+    __shared__ int s_wave[PERM_WAVES * MOE_MAX_E];
+    permute_indices(idx, N, E, counts, offsets, perm, inv_perm, true, s_cnt, s_off, s_wave,
+                    nullptr);
+}
+
+// xg[i,:] = x[perm[i]/k,:]; one workgroup of 256 threads per group of rows.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const int32_t* __restrict__ perm, int N,
+                                                          int k, const uint4* __restrict__ x,
+                                                          int row_chunks,
+                                                          uint4* __restrict__ xg) {
+    for (int i = blockIdx.x; i < N; i += gridDim.x) {
+        const uint4* src = x + (size_t)(perm[i] / k) * row_chunks;
+        uint4* dst = xg + (size_t)i * row_chunks;
+        for (int c = threadIdx.x; c < row_chunks; c += 256) dst[c] = src[c];
+    }
+}
+
+int moe_permute_launch(const int32_t* idx, int T, int E, int k, const void* x, int d,
+                       moe_dtype_t x_dtype, int32_t* counts, int32_t* offsets, int32_t* perm,
+                       int32_t* inv_perm, void* xg, hipStream_t s) {
+    const int N = T * k;
+    const int row_chunks = (int)(((size_t)d * (x_dtype == MOE_BF16 ? 2 : 4)) / 16);
+    if (N <= PERM_THREADS) {
+        unsigned grid = 1;
+        if (x != nullptr && N > 0) grid = (unsigned)(N < 64 ? N : 64);
+        hipLaunchKernelGGL(permute_small_kernel, dim3(grid), dim3(PERM_THREADS), 0, s, idx, N, E, k,
+                           (const uint4*)x, row_chunks, counts, offsets, perm, inv_perm,
+                           (uint4*)xg);
+        return moe_launch_status();
+    }
+    hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(PERM_THREADS), 0, s, idx, N, E, counts,
+                       offsets, perm, inv_perm);
+    if (moe_launch_status() != MOE_OK) return MOE_ERR_HIP;
+    if (x != nullptr) {
+        unsigned grid = (unsigned)(N < 8192 ? N : 8192);
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(256), 0, s, perm, N, k,
+                           (const uint4*)x, row_chunks, (uint4*)xg);
+    }
+    return moe_launch_status();
+}
+
+// ---------------------------------------------------------------- combine ----
+
+__global__ __launch_bounds__(256) void combine_kernel(const float4* __restrict__ yg,
+                                                      const int32_t* __restrict__ inv_perm,
+                                                      const float* __restrict__ weights, int T,
+                                                      int k, int row_chunks /* d/4 */,
+                                                      float4* __restrict__ y) {
+    const int t = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T || c >= row_chunks) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; j++) {
+        const float w = weights[(size_t)t * k + j];
+        const float4 v = yg[(size_t)inv_perm[(size_t)t * k + j] * row_chunks + c];
+        acc.x += w * v.x;
+        acc.y += w * v.y;
+        acc.z += w * v.z;
+        acc.w += w * v.w;
+    }
+    y[(size_t)t * row_chunks + c] = acc;
+}
+
+int moe_combine_launch(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
+                       int d, float* y, hipStream_t s) {
+    const int row_chunks = d / 4;
+    dim3 grid((unsigned)((row_chunks + 255) / 256), (unsigned)T);
+    // gridDim.y is limited to 65535: walk T in slabs
+    for (int t0 = 0; t0 < T; t0 += 65535) {
+        const int tn = (T - t0) < 65535 ? (T - t0) : 65535;
+        grid.y = (unsigned)tn;
+        hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, s, (const float4*)yg,
+                           inv_perm + (size_t)t0 * k, weights + (size_t)t0 * k, tn, k, row_chunks,
+                           (float4*)(y + (size_t)t0 * d));
+    }
+    return moe_launch_status();
+}
+
+// ------------------------------------------------- stack support kernels ----
+
+__device__ __forceinline__ float block_sum_256(float v, float* s_red /*[4]*/) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return s_red[0] + s_red[1] + s_red[2] + s_red[3];
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, int d, float eps,
+                                                      float* __restrict__ h) {
+    __shared__ float s_red[4];
+    const float* row = x + (size_t)blockIdx.x * d;
+    float ss = 0.f;
+    for (int r = threadIdx.x; r < d; r += 256) ss += row[r] * row[r];
+    ss = block_sum_256(ss, s_red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    float* out = h + (size_t)blockIdx.x * d;
+    for (int r = threadIdx.x; r < d; r += 256) out[r] = row[r] * inv;
+}
+
+// One workgroup per token; thread r-strided partial sums for all E logits.
+__global__ __launch_bounds__(256) void router_logits_kernel(const float* __restrict__ h,
+                                                            const float* __restrict__ w_gate, int d,
+                                                            int E, float* __restrict__ logits) {
+    __shared__ float s_red[4];
+    const float* row = h + (size_t)blockIdx.x * d;
+    for (int e0 = 0; e0 < E; e0 += 8) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const int ne = (E - e0) < 8 ? (E - e0) : 8;
+        for (int r = threadIdx.x; r < d; r += 256) {
+            const float hv = row[r];
+            const float* wr = w_gate + (size_t)r * E + e0;
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (j < ne) acc[j] += hv * wr[j];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const float tot = block_sum_256(acc[j], s_red);
+            if (j < ne && threadIdx.x == 0) logits[(size_t)blockIdx.x * E + e0 + j] = tot;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void residual_add_kernel(float4* __restrict__ x,
+                                                           const float4* __restrict__ y,
+                                                           size_t n4) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        float4 a = x[i];
+        const float4 b = y[i];
+        a.x += b.x;
+        a.y += b.y;
+        a.z += b.z;
+        a.w += b.w;
+        x[i] = a;
+    }
+}
+
+int moe_rmsnorm_launch(const float* x, int T, int d, float eps, float* h, hipStream_t s) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3((unsigned)T), dim3(256), 0, s, x, d, eps, h);
+    return moe_launch_status();
+}
+
+int moe_router_logits_launch(const float* h, const float* w_gate, int T, int d, int E,
+                             float* logits, hipStream_t s) {
+    hipLaunchKernelGGL(router_logits_kernel, dim3((unsigned)T), dim3(256), 0, s, h, w_gate, d, E,
+                       logits);
+    return moe_launch_status();
+}
+
+int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t s) {
+    const size_t n4 = (size_t)T * d / 4;
+    size_t blocks = (n4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(residual_add_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (float4*)x,
+                       (const float4*)y, n4);
+    return moe_launch_status();
+}
