@@ -181,6 +181,9 @@ def main():
     ap.add_argument("--workload", default="decode_t1", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (a known-size reference dispatch "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -226,6 +229,14 @@ def main():
         step.run(sets[0], xs[i], lgs[i])
         torch.cuda.synchronize()
         counts_all.append(step.perm_out[0].cpu().tolist())
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB write
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     run_range(warmup)
     torch.cuda.synchronize()
