@@ -28,6 +28,8 @@
 #define GG_TILE_BLOCKS 16  // 16-row blocks per token tile (256 rows)
 #define GG_FROWS 16        // weight fragment rows per workgroup tile (256 features)
 #define GG_THREADS 512
+#define GG_NS 4              // LDS stages in flight
+#define GG_LOADS_PER_WAVE 4  // fragments each wave brings in per stage (32 / 8 waves)
 
 // ---- segment bookkeeping: expert e owns blocks [bbase_e, bbase_e + ceil(M_e/16)) ----
 struct SegInfo {
@@ -127,54 +129,114 @@ struct GroupedArgs {
     int C;       // down: d (row length of yg)
 };
 
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
+// vmcnt = bits 3:0 and 15:14, expcnt 6:4 = 7 and lgkmcnt 11:8 = 15 left open).
+#define GG_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+#define GG_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+
+// Wait until at most `batches` of this wave's stage loads (GG_LOADS_PER_WAVE each) are in flight.
+__device__ __forceinline__ void gg_wait_batches(int batches) {
+    if (batches >= 3) GG_WAIT_VMCNT(3 * GG_LOADS_PER_WAVE);
+    else if (batches == 2) GG_WAIT_VMCNT(2 * GG_LOADS_PER_WAVE);
+    else if (batches == 1) GG_WAIT_VMCNT(1 * GG_LOADS_PER_WAVE);
+    else GG_WAIT_VMCNT(0);
+}
+
+// Logical tile index -> (expert segment, tile inside the segment, feature tile).
+// Logical order: expert, then feature tile, then token tile (fastest), so that
+// workgroups with neighbouring indices share the same weight tile.
+__device__ __forceinline__ bool gg_find_logical(const int32_t* __restrict__ offsets, int E, int N,
+                                                int NT, int xcd, int slot, SegInfo& si,
+                                                int& tile_in_seg, int& nt) {
+    int total = 0, prev = 0;
+    for (int e = 0; e < E; e++) {
+        const int lo = gg_clamp_off(offsets[e], prev, N);
+        const int hi = gg_clamp_off(offsets[e + 1], lo, N);
+        prev = lo;
+        total += ((hi - lo + 16 * GG_TILE_BLOCKS - 1) / (16 * GG_TILE_BLOCKS)) * NT;
+    }
+    // Workgroup ids are dealt round-robin to the 8 XCDs (one L2 each): give every XCD
+    // one contiguous eighth of the logical order.
+    const int per_xcd = (total + 7) / 8;
+    if (slot >= per_xcd) return false;
+    const int L = xcd * per_xcd + slot;
+    if (L >= total) return false;
+    int base = 0, bb = 0;
+    prev = 0;
+    for (int e = 0; e < E; e++) {
+        const int lo = gg_clamp_off(offsets[e], prev, N);
+        const int hi = gg_clamp_off(offsets[e + 1], lo, N);
+        prev = lo;
+        const int nb = (hi - lo + 15) / 16;
+        const int tiles = (nb + GG_TILE_BLOCKS - 1) / GG_TILE_BLOCKS;
+        if (L < base + tiles * NT) {
+            const int r = L - base;
+            nt = r / tiles;
+            tile_in_seg = r % tiles;
+            si.e = e; si.row0 = lo; si.rows = hi - lo; si.bbase = bb;
+            return true;
+        }
+        base += tiles * NT;
+        bb += nb;
+    }
+    return false;
+}
+
+// Grouped GEMM tile: 256 token rows x 16 weight fragment rows, 8 waves.
+//
+// The reduction advances one MFMA step (32 indices) per stage; a stage is 16 A
+// fragments (weights) + 16 B fragments (token blocks) = 32 KiB, brought into a
+// ring of GG_NS stages in LDS by direct-to-LDS loads (each wave instruction
+// moves one whole fragment; no registers, no LDS store instructions).
+//
+// The two waves that share a SIMD (wave w and w+4; they own the two token
+// halves) run half a period apart: while one reads its 12 fragments of stage
+// k from LDS, the other issues the 32 MFMAs of the stage it read before, and
+// a workgroup barrier separates the half-periods.  Time slot t: group 0 reads
+// stage k at t = 2k and multiplies at t = 2k+1; group 1 reads at 2k+1 and
+// multiplies at 2k+2.  Stage j's LDS buffer is free again from slot 2j+2, and
+// that is when every wave issues its share of stage j+GG_NS.
 template <bool UP>
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
-    // stage = 32 A fragments (16 fragment rows x 2 steps) + 32 B fragments (16 blocks x 2 steps)
     extern __shared__ __align__(16) unsigned char smem[];
-    u32x4_t* lds = (u32x4_t*)smem;  // [2 stages][64 fragments][64 lanes]
+    u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][32 fragments][64 lanes]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nt = blockIdx.x % a.NT;
-    const int tt = blockIdx.x / a.NT;
     SegInfo si;
-    int tis;
-    if (!gg_find_tile(a.offsets, a.E, a.N, tt, si, tis)) return;
+    int tis, nt;
+    if (!gg_find_logical(a.offsets, a.E, a.N, a.NT, blockIdx.x & 7, blockIdx.x >> 3, si, tis, nt))
+        return;
     const int seg_blocks = (si.rows + 15) / 16;
     const int blk0 = tis * GG_TILE_BLOCKS;  // first block of this tile inside the segment
     const int nblk = (seg_blocks - blk0) < GG_TILE_BLOCKS ? (seg_blocks - blk0) : GG_TILE_BLOCKS;
 
-    const int wt = wave >> 2;  // token half: blocks [8*wt, 8*wt+8)
+    const int wt = wave >> 2;  // token half: blocks [8*wt, 8*wt+8); also the ping-pong group
     const int wn = wave & 3;   // fragment rows [4*wn, 4*wn+4)
     const int my_blocks = (nblk - 8 * wt) < 0 ? 0 : ((nblk - 8 * wt) > 8 ? 8 : (nblk - 8 * wt));
 
-    // global fragment bases
-    const size_t a_base = ((size_t)si.e * a.FR + (size_t)nt * GG_FROWS) * a.KS;  // + fr*KS + ks
-    const size_t b_base = ((size_t)(si.bbase + blk0)) * a.KS;                   // + blk*KS + ks
-
-    // loader role: wave w moves fragments 8w..8w+7 of the 64 in a stage.
-    // fragment q < 32: A, fragment row q/2, step q%2; q >= 32: B, block (q-32)/2, step q%2.
-    u32x4_t stage_reg[8];
+    // loader role: wave w moves fragments 4w..4w+3 of the 32 in a stage
+    // (q < 16: A fragment row q; q >= 16: B block q-16, clamped to an existing block so
+    // that every wave always issues the same number of loads).
+    const u32x4_t* src[GG_LOADS_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < 8; i++) stage_reg[i] = u32x4_t{0u, 0u, 0u, 0u};
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-            const int q = wave * 8 + i;
-            const int step = kt * 2 + (q & 1);
-            if (q < 32) {
-                stage_reg[i] = a.wfrag[(a_base + (size_t)(q >> 1) * a.KS + step) * 64 + lane];
-            } else {
-                const int blk = (q - 32) >> 1;
-                if (blk < nblk)
-                    stage_reg[i] = a.bfrag[(b_base + (size_t)blk * a.KS + step) * 64 + lane];
-            }
+    for (int i = 0; i < GG_LOADS_PER_WAVE; i++) {
+        const int q = wave * GG_LOADS_PER_WAVE + i;
+        if (q < 16) {
+            src[i] = a.wfrag + (((size_t)si.e * a.FR + (size_t)nt * GG_FROWS + q) * a.KS) * 64 + lane;
+        } else {
+            int blk = q - 16;
+            blk = blk < nblk ? blk : nblk - 1;
+            src[i] = a.bfrag + (((size_t)(si.bbase + blk0 + blk)) * a.KS) * 64 + lane;
         }
-    };
-    auto lstore = [&](int buf) {
+    }
+    auto issue_stage = [&](int j) {
+        const int buf = j % GG_NS;
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            const int q = wave * 8 + i;
-            lds[((size_t)buf * 64 + q) * 64 + lane] = stage_reg[i];
+        for (int i = 0; i < GG_LOADS_PER_WAVE; i++) {
+            const int q = wave * GG_LOADS_PER_WAVE + i;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(src[i] + (size_t)j * 64),
+                (__attribute__((address_space(3))) void*)(lds + (buf * 32 + q) * 64), 16, 0, 0);
         }
     };
 
@@ -183,36 +245,64 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     for (int i = 0; i < 8; i++)
 #pragma unroll
         for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    const int KT = a.KS / 2;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; kt++) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) gload(kt + 1);
+    bf16x8_t af[4], bfr[8];
+    auto read_frags = [&](int k) {
+        const int buf = k % GG_NS;
 #pragma unroll
-        for (int step = 0; step < 2; step++) {
-            bf16x8_t af[4];
+        for (int j = 0; j < 4; j++)
+            af[j] = __builtin_bit_cast(bf16x8_t, lds[(buf * 32 + 4 * wn + j) * 64 + lane]);
 #pragma unroll
-            for (int j = 0; j < 4; j++)
-                af[j] = __builtin_bit_cast(
-                    bf16x8_t, lds[((size_t)buf * 64 + (4 * wn + j) * 2 + step) * 64 + lane]);
+        for (int i = 0; i < 8; i++)
+            if (i < my_blocks)
+                bfr[i] = __builtin_bit_cast(bf16x8_t, lds[(buf * 32 + 16 + 8 * wt + i) * 64 + lane]);
+        GG_WAIT_LGKM0();
+    };
+    auto mma = [&]() {
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                if (i < my_blocks) {
-                    const bf16x8_t bfr = __builtin_bit_cast(
-                        bf16x8_t,
-                        lds[((size_t)buf * 64 + 32 + (8 * wt + i) * 2 + step) * 64 + lane]);
+        for (int i = 0; i < 8; i++)
+            if (i < my_blocks) {
 #pragma unroll
-                    for (int j = 0; j < 4; j++)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], bfr, acc[i][j],
-                                                                            0, 0, 0);
-                }
+                for (int j = 0; j < 4; j++)
+                    acc[i][j] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], bfr[i], acc[i][j], 0, 0, 0);
             }
+    };
+
+    const int KT = a.KS;
+    for (int j = 0; j < GG_NS && j < KT; j++) issue_stage(j);
+    gg_wait_batches((KT - 1) < (GG_NS - 1) ? (KT - 1) : (GG_NS - 1));
+    __builtin_amdgcn_s_barrier();
+    if (wt == 0) {
+        for (int k = 0; k < KT; k++) {
+            // slot 2k: read stage k (and refill the buffer stage k-1 has left)
+            if (k >= 1 && k + GG_NS - 1 < KT) issue_stage(k + GG_NS - 1);
+            read_frags(k);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // slot 2k+1: multiply stage k; before leaving, stage k+1 must have landed
+            mma();
+            __builtin_amdgcn_sched_barrier(0);
+            if (k + 1 < KT) gg_wait_batches((KT - 2 - k) < (GG_NS - 2) ? (KT - 2 - k) : (GG_NS - 2));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < KT) lstore(buf ^ 1);
-        __syncthreads();
+    } else {
+        __builtin_amdgcn_s_barrier();  // slot 0: idle
+        for (int k = 0; k < KT; k++) {
+            // slot 2k+1: read stage k; before leaving, stage k+1 must have landed
+            read_frags(k);
+            if (k + 1 < KT) gg_wait_batches((KT - 2 - k) < (GG_NS - 2) ? (KT - 2 - k) : (GG_NS - 2));
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // slot 2k+2: stage k's buffer is free: refill it, then multiply stage k
+            if (k + GG_NS < KT) issue_stage(k + GG_NS);
+            mma();
+            __builtin_amdgcn_sched_barrier(0);
+            if (k + 1 < KT) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // ---- epilogue ----
@@ -275,7 +365,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
     const int max_tiles = N / (16 * GG_TILE_BLOCKS) + E;
-    const size_t lds_bytes = 2 * 64 * MOE_FRAG_BYTES;
+    const size_t lds_bytes = GG_NS * 32 * MOE_FRAG_BYTES;
 
     static bool attr_set = false;
     if (!attr_set) {
@@ -304,7 +394,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.NT = up.FR / GG_FROWS;
     up.KS_out = f / 32;
     up.C = 0;
-    hipLaunchKernelGGL(gg_gemm_kernel<true>, dim3((unsigned)(up.NT * max_tiles)), dim3(GG_THREADS),
+    hipLaunchKernelGGL(gg_gemm_kernel<true>, dim3((unsigned)((up.NT * max_tiles + 7) / 8 * 8)), dim3(GG_THREADS),
                        lds_bytes, s, up);
     moe_record_mid_event(s);
 
@@ -319,7 +409,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.NT = dn.FR / GG_FROWS;
     dn.KS_out = 0;
     dn.C = d;
-    hipLaunchKernelGGL(gg_gemm_kernel<false>, dim3((unsigned)(dn.NT * max_tiles)), dim3(GG_THREADS),
+    hipLaunchKernelGGL(gg_gemm_kernel<false>, dim3((unsigned)((dn.NT * max_tiles + 7) / 8 * 8)), dim3(GG_THREADS),
                        lds_bytes, s, dn);
     return moe_launch_status();
 }
