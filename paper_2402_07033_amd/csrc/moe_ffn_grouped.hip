@@ -210,8 +210,41 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     const int blk0 = tis * GG_TILE_BLOCKS;  // first block of this tile inside the segment
     const int nblk = (seg_blocks - blk0) < GG_TILE_BLOCKS ? (seg_blocks - blk0) : GG_TILE_BLOCKS;
 
-    const int wt = wave >> 2;  // token half: blocks [8*wt, 8*wt+8); also the ping-pong group
-    const int wn = wave & 3;   // fragment rows [4*wn, 4*wn+4)
+    // The ping-pong groups must pair the two waves that share a SIMD.  Read the SIMD
+    // each wave actually landed on (HW_ID bits 5:4): the first wave on a SIMD joins
+    // group 0, the second group 1.  If the placement is not 2 waves per SIMD, fall back
+    // to halves by wave index (still correct, only less overlap).
+    __shared__ int s_simd[8];
+    if (lane == 0) s_simd[wave] = (int)__builtin_amdgcn_s_getreg((1 << 11) | (4 << 6) | 4);
+    __syncthreads();
+    int wt = wave >> 2;  // token half: blocks [8*wt, 8*wt+8); also the ping-pong group
+    int wn = wave & 3;   // fragment rows [4*wn, 4*wn+4)
+    {
+        int grp[8], cnt0 = 0, cnt1 = 0;
+        bool ok = true;
+#pragma unroll
+        for (int w = 0; w < 8; w++) {
+            int rank = 0;
+#pragma unroll
+            for (int v = 0; v < 8; v++)
+                if (v < w && s_simd[v] == s_simd[w]) rank++;
+            grp[w] = rank;
+            if (rank == 0) cnt0++;
+            else if (rank == 1) cnt1++;
+            else ok = false;
+        }
+        if (ok && cnt0 == 4 && cnt1 == 4) {
+            int g = 0, n = 0;
+#pragma unroll
+            for (int w = 0; w < 8; w++)
+                if (w == wave) g = grp[w];
+#pragma unroll
+            for (int w = 0; w < 8; w++)
+                if (w < wave && grp[w] == g) n++;
+            wt = g;
+            wn = n;
+        }
+    }
     const int my_blocks = (nblk - 8 * wt) < 0 ? 0 : ((nblk - 8 * wt) > 8 ? 8 : (nblk - 8 * wt));
 
     // loader role: wave w moves fragments 4w..4w+3 of the 32 in a stage
@@ -257,16 +290,17 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
                 bfr[i] = __builtin_bit_cast(bf16x8_t, lds[(buf * 32 + 16 + 8 * wt + i) * 64 + lane]);
         GG_WAIT_LGKM0();
     };
-    auto mma = [&]() {
+    auto mma_range = [&](int i0, int i1) {
 #pragma unroll
         for (int i = 0; i < 8; i++)
-            if (i < my_blocks) {
+            if (i >= i0 && i < i1 && i < my_blocks) {
 #pragma unroll
                 for (int j = 0; j < 4; j++)
                     acc[i][j] =
                         __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], bfr[i], acc[i][j], 0, 0, 0);
             }
     };
+    auto mma = [&]() { mma_range(0, 8); };
 
     const int KT = a.KS;
     for (int j = 0; j < GG_NS && j < KT; j++) issue_stage(j);
@@ -297,8 +331,9 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             // slot 2k+2: stage k's buffer is free: refill it, then multiply stage k
+            mma_range(0, 2);
             if (k + GG_NS < KT) issue_stage(k + GG_NS);
-            mma();
+            mma_range(2, 8);
             __builtin_amdgcn_sched_barrier(0);
             if (k + 1 < KT) __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
