@@ -33,6 +33,10 @@ WORKLOADS = {
     "decode_t1": dict(T=1, x_bf16=False, zipf=None, bound="hbm"),
     "beam_t16": dict(T=16, x_bf16=False, zipf=1.2, bound="hbm"),
     "prefill_t4096": dict(T=4096, x_bf16=True, zipf=1.2, bound="mfma"),
+    # 32-layer stack of MoE blocks (RMSNorm -> router -> experts -> residual), all ~90 GB of
+    # expert matrices resident; a step is one pass through all layers
+    "stack_t1": dict(T=1, x_bf16=False, zipf=None, bound="hbm", layers=32),
+    "stack_t512": dict(T=512, x_bf16=False, zipf=None, bound="hbm", layers=32),
 }
 D, F, E, K = 4096, 14336, 8, 2
 
@@ -173,6 +177,100 @@ def cpu_baseline(torch, wl, host_w, xs, lgs, budget_s=15.0):
                        f"one weight set, {t_used:.1f} s of fp64 CPU work")
 
 
+def run_stack(args, torch, moe, wl):
+    """Layer-stack workload: value = tokens/s through all layers, ms_per_step = stack time."""
+    T, L = wl["T"], (args.layers if args.layers is not None else wl["layers"])
+    steps = args.steps if args.steps is not None else (20 if T == 1 else 5)
+    warmup = args.warmup if args.warmup is not None else 2
+    g = torch.Generator(device="cuda")
+    g.manual_seed(777)
+    layers, host_w, host_gate = [], None, None
+    for li in range(L):
+        W, src = make_weight_set(torch, moe, 2000 + li)
+        wg = (torch.randn((D, E), generator=g, device="cuda") * D ** -0.5).contiguous()
+        if li == 0 and not args.no_cpu_baseline:
+            host_w = tuple(t.cpu() for t in src)
+            host_gate = wg.cpu()
+        del src
+        layers.append((W, wg))
+    torch.cuda.empty_cache()
+    x0 = torch.randn((T, D), generator=g, device="cuda")
+    x = torch.empty_like(x0)
+    bufs = moe.StackBuffers(T, E, K, D, F)
+    stream = torch.cuda.current_stream().cuda_stream
+    events = HipEvents()
+
+    def one_pass(ev=None):
+        x.copy_(x0)
+
+        def on_layer(li):
+            if ev is not None:
+                moe.moe_set_ffn_mid_event(ev[li][1])
+                events.record(ev[li][0], stream)
+        idx_out = [] if ev is not None else None
+        moe.moe_stack_forward(layers, x, K, bufs=bufs, on_layer=on_layer, idx_out=idx_out)
+        return idx_out
+
+    for _ in range(warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_pass()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    # one more pass with events around each layer's first projection
+    ev = [(events.create(), events.create()) for _ in range(L)]
+    idx_out = one_pass(ev)
+    moe.moe_set_ffn_mid_event(None)
+    torch.cuda.synchronize()
+    up_ms = sum(events.elapsed_ms(a, b) for a, b in ev)
+    n_active = sum(len(set(t.cpu().flatten().tolist())) for t in idx_out)
+    up_bytes = n_active * 2 * D * F * 2
+    achieved = up_bytes / (up_ms * 1e-3) / 1e9
+    all_bytes = n_active * 3 * D * F * 2
+    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBS, traffic=None,
+                    kernel="first projection of moe_expert_ffn, summed over the layers",
+                    kernel_ms=up_ms, active_experts_all_layers=n_active,
+                    whole_stack_GBs=all_bytes / (ms_per_step * 1e-3) / 1e9,
+                    whole_stack_TFLOPs=T * K * 6 * D * F * L / (ms_per_step * 1e-3) / 1e12)
+    result = {
+        "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights x fp32 activations" + (" (bf16 hi+lo)" if T * K <= 32 else
+                                                      " (rounded to bf16)") + ", fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "layers": L, "d_model": D, "d_ff": F,
+                   "experts": E, "top_k": K,
+                   "per_token_expert_time_us": ms_per_step * 1e3 / T,
+                   "resident_expert_bytes": sum(W.nbytes for W, _ in layers)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        # the oracle on a bounded sample: up to 4 tokens through ONE layer; the stack rate is
+        # that per-layer rate divided by the number of layers (labelled extrapolated)
+        import numpy as np
+        from oracle import moe_oracle as orc
+        w1, w3, w2 = (t.view(torch.int16).numpy().view(np.uint16) for t in host_w)
+        n_tok = min(T, 4)
+        xs = x0[:n_tok].cpu().numpy().astype(np.float64)
+        reps, t_used = 0, 0.0
+        while t_used < 10.0 and reps < 8:
+            t0 = time.perf_counter()
+            orc.stack(xs, [(host_gate.numpy(), w1, w3, w2)], K)
+            t_used += time.perf_counter() - t0
+            reps += 1
+        per_layer_tokens_s = reps * n_tok / t_used
+        result["cpu_baseline"] = dict(
+            value=per_layer_tokens_s / L, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+            sample=f"{reps} x {n_tok} tokens through 1 layer ({t_used:.1f} s of fp64 CPU work); "
+                   f"stack rate extrapolated as the one-layer rate / {L} layers")
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -197,6 +295,8 @@ def main():
 
     wl = WORKLOADS[args.workload]
     T = wl["T"]
+    if "layers" in wl:
+        return run_stack(args, torch, moe, wl)
     decode_like = wl["bound"] == "hbm"
     steps = args.steps if args.steps is not None else (400 if decode_like else 30)
     warmup = args.warmup if args.warmup is not None else (40 if decode_like else 5)

@@ -126,3 +126,24 @@ def router_logits(h: np.ndarray, w_gate: np.ndarray) -> np.ndarray:
     _check(lib().oracle_router_logits(_p(h), _p(w_gate), C.c_long(T), C.c_long(d), C.c_int(E),
                                       _p(out)), "router_logits")
     return out
+
+
+def stack(x0: np.ndarray, layers, k: int, eps: float = 1e-5, forced_logits=None) -> dict:
+    """Layer stack: per layer h = rmsnorm(x); logits = fp32(h . W_g); y = layer(h, logits);
+    x <- x + y.  layers: list of (w_gate fp32 [d,E], w1, w3, w2).  With forced_logits (one
+    fp32 [T,E] array per layer) routing uses those logits instead of the oracle's own
+    (teacher forcing, so that routing can be compared bit for bit while activations drift
+    within tolerance).  Returns the final x, every layer's routing indices and the oracle's
+    own logits."""
+    x = np.array(x0, dtype=np.float64)
+    idx_all, own_logits = [], []
+    for li, (w_gate, w1, w3, w2) in enumerate(layers):
+        h = rmsnorm(x, eps)
+        lg_own = router_logits(h, w_gate)
+        own_logits.append(lg_own)
+        lg = lg_own if forced_logits is None else np.ascontiguousarray(forced_logits[li],
+                                                                       dtype=np.float32)
+        out = layer(h, lg, w1, w3, w2, k)
+        idx_all.append(out["idx"])
+        x = x + out["y"]
+    return dict(x=x, idx=idx_all, logits=own_logits)

@@ -261,3 +261,52 @@ def moe_layer(W: PackedWeights, x: torch.Tensor, logits: torch.Tensor, k: int,
     y = moe_combine(yg, inv_perm, w, stream=stream)
     return dict(idx=idx, w=w, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm,
                 xg=xg, yg=yg, y=y)
+
+
+class StackBuffers:
+    """Preallocated device buffers for moe_stack_forward (one layer's worth, reused)."""
+
+    def __init__(self, T: int, E: int, k: int, d: int, f: int, device="cuda"):
+        N = T * k
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.h = torch.empty((T, d), **f32)
+        self.logits = torch.empty((T, E), **f32)
+        self.idx = torch.empty((T, k), **i32)
+        self.w = torch.empty((T, k), **f32)
+        self.perm_out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
+                         torch.empty(N, **i32), torch.empty((N, d), **f32))
+        self.ws = torch.empty(max(moe_expert_ffn_workspace(N, E, d, f, MOE_F32), 256),
+                              dtype=torch.uint8, device=device)
+        self.yg = torch.empty((N, d), **f32)
+        self.y = torch.empty((T, d), **f32)
+
+
+def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=None,
+                      logits_out=None, idx_out=None, on_layer=None, stream=None):
+    """The layer-stack workload: for every (PackedWeights, w_gate) in `layers`
+        h = rmsnorm(x); logits = h . w_gate; y = moe_layer(h, logits); x += y
+    x (fp32 [T,d]) is updated in place.  logits_out / idx_out, when given, are lists
+    that receive a copy of every layer's router logits / expert indices.  on_layer(l)
+    is called before each layer's expert FFN is enqueued (measurement hook)."""
+    _dev(x, torch.float32, "x")
+    T, d = x.shape
+    W0 = layers[0][0]
+    if bufs is None:
+        bufs = StackBuffers(T, W0.E, k, d, W0.f, x.device)
+    for li, (W, w_gate) in enumerate(layers):
+        moe_rmsnorm(x, eps, bufs.h, stream=stream)
+        moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
+        moe_route(bufs.logits, k, bufs.idx, bufs.w, stream=stream)
+        _, offsets, _, inv_perm, xg = moe_permute(bufs.idx, W.E, bufs.h, out=bufs.perm_out,
+                                                  stream=stream)
+        if logits_out is not None:
+            logits_out.append(bufs.logits.clone())
+        if idx_out is not None:
+            idx_out.append(bufs.idx.clone())
+        if on_layer is not None:
+            on_layer(li)
+        moe_expert_ffn(W, xg, offsets, workspace=bufs.ws, yg=bufs.yg, stream=stream)
+        moe_combine(bufs.yg, inv_perm, bufs.w, bufs.y, stream=stream)
+        moe_residual_add(x, bufs.y, stream=stream)
+    return x

@@ -1,0 +1,88 @@
+"""GPU parity of the layer-stack workload (RMSNorm -> router logits -> MoE layer
+-> residual add, repeated) and of its support kernels.
+
+Routing is compared bit for bit under teacher forcing: the oracle's stack routes
+on the GPU's own fp32 router logits of every layer (its activations are fp64 and
+drift from the GPU's within tolerance, so its own logits may differ in the last
+bits and flip a near-tie).  The final activations must agree within 2e-2."""
+import numpy as np
+import pytest
+import torch
+
+import moe_inputs as mi
+from gpu_util import max_rel, pack_layer, to_dev, to_host
+from oracle import moe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def moe():
+    assert torch.cuda.is_available()
+    import paper_2402_07033_amd as m
+    m.lib()
+    return m
+
+
+def test_support_kernels(moe):
+    rng = np.random.default_rng(3)
+    for T, d, E in [(1, 4096, 8), (16, 256, 8), (513, 1024, 16), (40, 64, 3)]:
+        x = (rng.standard_normal((T, d)) * 3.0).astype(np.float32)
+        wg = (rng.standard_normal((d, E)) / np.sqrt(d)).astype(np.float32)
+        h_ref = orc.rmsnorm(x.astype(np.float64), 1e-5)
+        h = moe.moe_rmsnorm(to_dev(x), 1e-5)
+        assert max_rel(to_host(h), h_ref) <= 2e-6
+        lg_ref = orc.router_logits(to_host(h).astype(np.float64), wg)
+        lg = moe.moe_router_logits(h, to_dev(wg))
+        assert np.max(np.abs(to_host(lg) - lg_ref)) <= 1e-5 * max(1.0, np.max(np.abs(lg_ref)))
+        y = rng.standard_normal((T, d)).astype(np.float32)
+        xd = to_dev(x)
+        moe.moe_residual_add(xd, to_dev(y))
+        assert (to_host(xd) == x + y).all()
+
+
+def _run_stack(moe, cfgs, T, k):
+    """cfgs: one MoEConfig per layer.  Returns (gpu final x, oracle result, info)."""
+    host_layers, dev_layers = [], []
+    for cfg in cfgs:
+        w1, w3, w2 = mi.make_weights(cfg, threads=16)
+        w_gate = mi.normal_f32(cfg.seed, 1, (cfg.d, cfg.E), cfg.d ** -0.5)
+        li = mi.LayerInputs(cfg, None, None, w1, w3, w2, w_gate)
+        dev_layers.append((pack_layer(li), to_dev(w_gate)))
+        host_layers.append((w_gate, w1, w3, w2))
+    x0 = mi.normal_f32(cfgs[0].seed, 0, (T, cfgs[0].d))
+    xd = to_dev(x0.copy())
+    logits, idx = [], []
+    moe.moe_stack_forward(dev_layers, xd, k, logits_out=logits, idx_out=idx)
+    torch.cuda.synchronize()
+    gpu_logits = [to_host(t) for t in logits]
+    ref = orc.stack(x0.astype(np.float64), host_layers, k, forced_logits=gpu_logits)
+    for l in range(len(cfgs)):
+        assert (to_host(idx[l]) == ref["idx"][l]).all(), f"routing differs at layer {l}"
+    free = orc.stack(x0.astype(np.float64), host_layers, k)
+    same = np.mean([np.mean(a == b) for a, b in zip(free["idx"], ref["idx"])])
+    for W, _ in dev_layers:
+        W.free()
+    return to_host(xd), ref, dict(same_routing_free_running=float(same),
+                                  err_free=max_rel(to_host(xd), free["x"]))
+
+
+@pytest.mark.parametrize("T,L,d,f", [(1, 6, 256, 512), (24, 4, 256, 512), (300, 3, 256, 512),
+                                     (7, 4, 512, 1024)])
+def test_stack_small_shapes(moe, T, L, d, f):
+    cfgs = [mi.small_config(f"s{l}", T, d, f, 8, 2, 3000 + 10 * l + T, w_dtype=mi.BF16)
+            for l in range(L)]
+    x, ref, info = _run_stack(moe, cfgs, T, 2)
+    err = max_rel(x, ref["x"])
+    print(f"stack T={T} L={L} d={d}: err={err:.3e} {info}")
+    assert err <= TOL_BF16
+
+
+@pytest.mark.parametrize("T", [1, 16])
+def test_stack_mixtral_shape_two_layers(moe, T):
+    cfgs = [mi.stack_layer_config(l, T) for l in range(2)]
+    x, ref, info = _run_stack(moe, cfgs, T, 2)
+    err = max_rel(x, ref["x"])
+    print(f"stack mixtral T={T} L=2: err={err:.3e} {info}")
+    assert err <= TOL_BF16

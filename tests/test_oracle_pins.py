@@ -328,3 +328,24 @@ def test_zipf_pmf_and_seed_determinism():
     a = mi.make_layer(mi.CONFIGS["tiny_fp32"], threads=1)
     b = mi.make_layer(mi.CONFIGS["tiny_fp32"], threads=4)
     assert (a.w2 == b.w2).all() and (a.x == b.x).all() and (a.logits == b.logits).all()
+
+
+def test_stack_is_norm_route_layer_residual():
+    rng = np.random.default_rng(12)
+    T, d, f, E, k = 5, 8, 12, 4, 2
+    layers = []
+    for l in range(3):
+        cfg, li = _tiny(seed=50 + l, T=T, d=d, f=f, E=E, k=k)
+        layers.append((li.w_gate, li.w1, li.w3, li.w2))
+    x0 = rng.standard_normal((T, d))
+    out = orc.stack(x0, layers, k)
+    # written out by hand with numpy + the dense brute force
+    x = x0.copy()
+    for w_gate, w1, w3, w2 in layers:
+        h = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + 1e-5)
+        lg = (h @ w_gate.astype(np.float64)).astype(np.float32)
+        x = x + bf.layer(h, lg, mi.to_f64(w1), mi.to_f64(w3), mi.to_f64(w2), k)
+    assert _rel(out["x"], x) < 1e-12
+    # forcing the oracle's own logits changes nothing
+    forced = orc.stack(x0, layers, k, forced_logits=out["logits"])
+    assert (forced["x"] == out["x"]).all()
