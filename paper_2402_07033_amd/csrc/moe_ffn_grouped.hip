@@ -6,8 +6,7 @@
 // fragments (32 reduction indices x 16 token rows) per expert segment, padded
 // with zero rows to a multiple of 16, so that no tile straddles two experts
 // and the GEMM main loop has no bounds checks.  A fragment is 1 KiB: one
-// wavefront moves it with a single coalesced 16-byte-per-lane access, and the
-// LDS copy is read back conflict-free (lane l reads bytes 16l..16l+15).
+// wavefront moves it with a single coalesced 16-byte-per-lane access.
 //
 //   pack  : xg [N,d] (fp32 or bf16) -> xp fragments [block][d/32]
 //   up    : per (token tile of 256 rows, 128 h-columns): a = x.w1, b = x.w3,
@@ -15,21 +14,39 @@
 //           hp [block][f/32] for the second GEMM
 //   down  : per (token tile of 256 rows, 256 output features): yg = h.w2, fp32
 //
-// Workgroup: 8 waves as 2 (token halves of 128 rows) x 4 (groups of 4 weight
-// fragment rows = 64 features); each wave owns a 128 x 64 accumulator tile
-// (32 MFMA tiles, 128 registers).  The reduction advances 64 indices per
-// stage; stages are double-buffered in LDS (2 x 64 KiB).
-//
-// The grid covers the worst case number of token tiles (N/256 + E); a
-// workgroup finds its expert from the device-side offsets and leaves if its
-// tile does not exist, so the host never learns the per-expert sizes.
+// GEMM kernel (measured limits that shaped it: LDS reads 128 B/clk per CU,
+// vector-memory path ~50-64 B/clk per CU, one 256 x 256 x 32 step = 1024
+// matrix-core clocks per SIMD):
+//   * workgroup tile 256 tokens x 16 weight fragment rows, 4 waves, one per
+//     SIMD; wave w owns fragment rows 4w..4w+3 for ALL 16 token blocks:
+//     64 MFMA tiles = 256 accumulator registers (pinned to the accumulation
+//     register file through the inline-asm constraint).
+//   * weights (A) never touch LDS: each wave streams its own 4 fragments per
+//     step straight from global memory into a 4-deep register ring (the
+//     packed layout makes these 1 KiB coalesced loads with no redundancy
+//     between waves).
+//   * token fragments (B) are shared by the 4 waves through an 8-stage LDS ring
+//     filled by direct-to-LDS loads (no staging registers, no LDS stores);
+//     every wave reads the 16 B fragments of the next step while it issues the
+//     64 MFMAs of the current one (single register set, refilled in place right
+//     after its last use).  LDS traffic per step: 64 KiB reads + 16 KiB writes.
+//   * the vector-memory requests (4 direct-to-LDS + 4 weight loads per wave
+//     and step) and the 16 LDS reads are spread between the MFMAs, one barrier
+//     per step publishes the next stage.
+//   * the workgroup is persistent (one per CU) and the load stream runs across
+//     tile boundaries: while the last steps of a tile are multiplied, the first
+//     stages of the next tile are already being requested.
+//   * tiles are walked in an order that keeps a weight tile on one XCD (one L2):
+//     expert, then feature tile, then token tile, one contiguous eighth of that
+//     order per XCD.
 #include "moe_internal.h"
 
 #define GG_TILE_BLOCKS 16  // 16-row blocks per token tile (256 rows)
 #define GG_FROWS 16        // weight fragment rows per workgroup tile (256 features)
-#define GG_THREADS 512
-#define GG_NS 4              // LDS stages in flight
-#define GG_LOADS_PER_WAVE 4  // fragments each wave brings in per stage (32 / 8 waves)
+#define GG_THREADS 256
+#define GG_NS 8            // LDS stages of 16 B fragments (16 KiB each)
+#define GG_PA 4            // depth of the weight-fragment register ring (steps)
+#define GG_VMEM_PER_STEP 8 // vector-memory requests per wave and step (4 B + 4 A)
 
 // ---- segment bookkeeping: expert e owns blocks [bbase_e, bbase_e + ceil(M_e/16)) ----
 struct SegInfo {
@@ -57,27 +74,6 @@ __device__ __forceinline__ bool gg_find_block(const int32_t* __restrict__ offset
             return true;
         }
         bb += nb;
-    }
-    return false;
-}
-
-// Locate token tile `tt` (tiles of GG_TILE_BLOCKS blocks, per expert).
-__device__ __forceinline__ bool gg_find_tile(const int32_t* __restrict__ offsets, int E, int N,
-                                             int tt, SegInfo& si, int& tile_in_seg) {
-    int bb = 0, tiles = 0, prev = 0;
-    for (int e = 0; e < E; e++) {
-        const int lo = gg_clamp_off(offsets[e], prev, N);
-        const int hi = gg_clamp_off(offsets[e + 1], lo, N);
-        prev = lo;
-        const int nb = (hi - lo + 15) / 16;
-        const int nt = (nb + GG_TILE_BLOCKS - 1) / GG_TILE_BLOCKS;
-        if (tt < tiles + nt) {
-            si.e = e; si.row0 = lo; si.rows = hi - lo; si.bbase = bb;
-            tile_in_seg = tt - tiles;
-            return true;
-        }
-        bb += nb;
-        tiles += nt;
     }
     return false;
 }
@@ -129,25 +125,22 @@ struct GroupedArgs {
     int C;       // down: d (row length of yg)
 };
 
-// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
-// vmcnt = bits 3:0 and 15:14, expcnt 6:4 = 7 and lgkmcnt 11:8 = 15 left open).
+// s_waitcnt with only one counter constrained (gfx9 encoding: vmcnt = bits 3:0 and
+// 15:14, expcnt = 6:4, lgkmcnt = 11:8; all-ones = no wait).
 #define GG_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-#define GG_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+#define GG_WAIT_LGKM(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
 
-// Wait until at most `batches` of this wave's stage loads (GG_LOADS_PER_WAVE each) are in flight.
-__device__ __forceinline__ void gg_wait_batches(int batches) {
-    if (batches >= 3) GG_WAIT_VMCNT(3 * GG_LOADS_PER_WAVE);
-    else if (batches == 2) GG_WAIT_VMCNT(2 * GG_LOADS_PER_WAVE);
-    else if (batches == 1) GG_WAIT_VMCNT(1 * GG_LOADS_PER_WAVE);
-    else GG_WAIT_VMCNT(0);
-}
+struct TileInfo {
+    SegInfo si;
+    int tis;   // token tile inside the segment
+    int nt;    // feature tile
+    int blk0;  // first block of the tile inside the segment
+    int nblk;  // blocks of the tile that exist (1..16)
+};
 
-// Logical tile index -> (expert segment, tile inside the segment, feature tile).
-// Logical order: expert, then feature tile, then token tile (fastest), so that
-// workgroups with neighbouring indices share the same weight tile.
-__device__ __forceinline__ bool gg_find_logical(const int32_t* __restrict__ offsets, int E, int N,
-                                                int NT, int xcd, int slot, SegInfo& si,
-                                                int& tile_in_seg, int& nt) {
+// Number of logical tiles = NT * sum_e ceil(M_e / 256).
+__device__ __forceinline__ int gg_total_tiles(const int32_t* __restrict__ offsets, int E, int N,
+                                              int NT) {
     int total = 0, prev = 0;
     for (int e = 0; e < E; e++) {
         const int lo = gg_clamp_off(offsets[e], prev, N);
@@ -155,14 +148,14 @@ __device__ __forceinline__ bool gg_find_logical(const int32_t* __restrict__ offs
         prev = lo;
         total += ((hi - lo + 16 * GG_TILE_BLOCKS - 1) / (16 * GG_TILE_BLOCKS)) * NT;
     }
-    // Workgroup ids are dealt round-robin to the 8 XCDs (one L2 each): give every XCD
-    // one contiguous eighth of the logical order.
-    const int per_xcd = (total + 7) / 8;
-    if (slot >= per_xcd) return false;
-    const int L = xcd * per_xcd + slot;
-    if (L >= total) return false;
-    int base = 0, bb = 0;
-    prev = 0;
+    return total;
+}
+
+// Logical tile index -> tile.  Logical order: expert, then feature tile, then token
+// tile (fastest), so that neighbouring indices share the same weight tile.
+__device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offsets, int E, int N,
+                                               int NT, int L, TileInfo& ti) {
+    int base = 0, bb = 0, prev = 0;
     for (int e = 0; e < E; e++) {
         const int lo = gg_clamp_off(offsets[e], prev, N);
         const int hi = gg_clamp_off(offsets[e + 1], lo, N);
@@ -171,9 +164,11 @@ __device__ __forceinline__ bool gg_find_logical(const int32_t* __restrict__ offs
         const int tiles = (nb + GG_TILE_BLOCKS - 1) / GG_TILE_BLOCKS;
         if (L < base + tiles * NT) {
             const int r = L - base;
-            nt = r / tiles;
-            tile_in_seg = r % tiles;
-            si.e = e; si.row0 = lo; si.rows = hi - lo; si.bbase = bb;
+            ti.nt = r / tiles;
+            ti.tis = r % tiles;
+            ti.si.e = e; ti.si.row0 = lo; ti.si.rows = hi - lo; ti.si.bbase = bb;
+            ti.blk0 = ti.tis * GG_TILE_BLOCKS;
+            ti.nblk = (nb - ti.blk0) < GG_TILE_BLOCKS ? (nb - ti.blk0) : GG_TILE_BLOCKS;
             return true;
         }
         base += tiles * NT;
@@ -182,202 +177,218 @@ __device__ __forceinline__ bool gg_find_logical(const int32_t* __restrict__ offs
     return false;
 }
 
-// Grouped GEMM tile: 256 token rows x 16 weight fragment rows, 8 waves.
-//
-// The reduction advances one MFMA step (32 indices) per stage; a stage is 16 A
-// fragments (weights) + 16 B fragments (token blocks) = 32 KiB, brought into a
-// ring of GG_NS stages in LDS by direct-to-LDS loads (each wave instruction
-// moves one whole fragment; no registers, no LDS store instructions).
-//
-// The two waves that share a SIMD (wave w and w+4; they own the two token
-// halves) run half a period apart: while one reads its 12 fragments of stage
-// k from LDS, the other issues the 32 MFMAs of the stage it read before, and
-// a workgroup barrier separates the half-periods.  Time slot t: group 0 reads
-// stage k at t = 2k and multiplies at t = 2k+1; group 1 reads at 2k+1 and
-// multiplies at 2k+2.  Stage j's LDS buffer is free again from slot 2j+2, and
-// that is when every wave issues its share of stage j+GG_NS.
+// MFMA with the accumulator pinned to the accumulation registers: 256 of them
+// are live per wave, and left to itself the register allocator shuffles them
+// through the vector registers inside the loop.
+__device__ __forceinline__ void gg_mfma(f32x4_t& c, const u32x4_t& a, const bf16x8_t& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+// Global source pointers of one tile for this wave (all wave-uniform).
+struct TileSrc {
+    const u32x4_t* a[4];  // this wave's 4 weight fragment rows (start of the reduction)
+    const u32x4_t* b[4];  // the 4 token blocks this wave requests into LDS
+};
+
+__device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo& ti, int wave,
+                                            TileSrc& ts) {
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+        ts.a[j] = a.wfrag +
+                  (((size_t)ti.si.e * a.FR + (size_t)ti.nt * GG_FROWS + 4 * wave + j) * a.KS) * 64;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        int blk = 4 * wave + i;
+        blk = blk < ti.nblk ? blk : ti.nblk - 1;  // clamp: every wave always issues 4 requests
+        ts.b[i] = a.bfrag + (((size_t)(ti.si.bbase + ti.blk0 + blk)) * a.KS) * 64;
+    }
+}
+
 template <bool UP>
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][32 fragments][64 lanes]
+    u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][16 fragments][64 lanes]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    SegInfo si;
-    int tis, nt;
-    if (!gg_find_logical(a.offsets, a.E, a.N, a.NT, blockIdx.x & 7, blockIdx.x >> 3, si, tis, nt))
-        return;
-    const int seg_blocks = (si.rows + 15) / 16;
-    const int blk0 = tis * GG_TILE_BLOCKS;  // first block of this tile inside the segment
-    const int nblk = (seg_blocks - blk0) < GG_TILE_BLOCKS ? (seg_blocks - blk0) : GG_TILE_BLOCKS;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // fragment rows [4*wave, +4)
+    const unsigned voff = (unsigned)lane * 16u;                  // byte offset inside a fragment
+    const int KT = a.KS;                                         // multiple of 4, >= GG_NS
 
-    // The ping-pong groups must pair the two waves that share a SIMD.  Read the SIMD
-    // each wave actually landed on (HW_ID bits 5:4): the first wave on a SIMD joins
-    // group 0, the second group 1.  If the placement is not 2 waves per SIMD, fall back
-    // to halves by wave index (still correct, only less overlap).
-    __shared__ int s_simd[8];
-    if (lane == 0) s_simd[wave] = (int)__builtin_amdgcn_s_getreg((1 << 11) | (4 << 6) | 4);
-    __syncthreads();
-    int wt = wave >> 2;  // token half: blocks [8*wt, 8*wt+8); also the ping-pong group
-    int wn = wave & 3;   // fragment rows [4*wn, 4*wn+4)
-    {
-        int grp[8], cnt0 = 0, cnt1 = 0;
-        bool ok = true;
-#pragma unroll
-        for (int w = 0; w < 8; w++) {
-            int rank = 0;
-#pragma unroll
-            for (int v = 0; v < 8; v++)
-                if (v < w && s_simd[v] == s_simd[w]) rank++;
-            grp[w] = rank;
-            if (rank == 0) cnt0++;
-            else if (rank == 1) cnt1++;
-            else ok = false;
-        }
-        if (ok && cnt0 == 4 && cnt1 == 4) {
-            int g = 0, n = 0;
-#pragma unroll
-            for (int w = 0; w < 8; w++)
-                if (w == wave) g = grp[w];
-#pragma unroll
-            for (int w = 0; w < 8; w++)
-                if (w < wave && grp[w] == g) n++;
-            wt = g;
-            wn = n;
-        }
-    }
-    const int my_blocks = (nblk - 8 * wt) < 0 ? 0 : ((nblk - 8 * wt) > 8 ? 8 : (nblk - 8 * wt));
-
-    // loader role: wave w moves fragments 4w..4w+3 of the 32 in a stage
-    // (q < 16: A fragment row q; q >= 16: B block q-16, clamped to an existing block so
-    // that every wave always issues the same number of loads).
-    const u32x4_t* src[GG_LOADS_PER_WAVE];
-#pragma unroll
-    for (int i = 0; i < GG_LOADS_PER_WAVE; i++) {
-        const int q = wave * GG_LOADS_PER_WAVE + i;
-        if (q < 16) {
-            src[i] = a.wfrag + (((size_t)si.e * a.FR + (size_t)nt * GG_FROWS + q) * a.KS) * 64 + lane;
-        } else {
-            int blk = q - 16;
-            blk = blk < nblk ? blk : nblk - 1;
-            src[i] = a.bfrag + (((size_t)(si.bbase + blk0 + blk)) * a.KS) * 64 + lane;
-        }
-    }
-    auto issue_stage = [&](int j) {
-        const int buf = j % GG_NS;
-#pragma unroll
-        for (int i = 0; i < GG_LOADS_PER_WAVE; i++) {
-            const int q = wave * GG_LOADS_PER_WAVE + i;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(src[i] + (size_t)j * 64),
-                (__attribute__((address_space(3))) void*)(lds + (buf * 32 + q) * 64), 16, 0, 0);
-        }
+    // this workgroup's tiles: logical indices xcd*per_xcd + slot, slot = id/8, id/8 + wgs, ...
+    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
+    const int per_xcd = (total + 7) / 8;
+    const int xcd = blockIdx.x & 7;
+    const int wgs_per_xcd = gridDim.x >> 3;
+    int slot = blockIdx.x >> 3;
+    auto tile_at = [&](int sl, TileInfo& ti) -> bool {
+        if (sl >= per_xcd) return false;
+        const int L = xcd * per_xcd + sl;
+        return L < total && gg_decode_tile(a.offsets, a.E, a.N, a.NT, L, ti);
     };
 
-    f32x4_t acc[8][4];
-#pragma unroll
-    for (int i = 0; i < 8; i++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    bf16x8_t af[4], bfr[8];
-    auto read_frags = [&](int k) {
-        const int buf = k % GG_NS;
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-            af[j] = __builtin_bit_cast(bf16x8_t, lds[(buf * 32 + 4 * wn + j) * 64 + lane]);
-#pragma unroll
-        for (int i = 0; i < 8; i++)
-            if (i < my_blocks)
-                bfr[i] = __builtin_bit_cast(bf16x8_t, lds[(buf * 32 + 16 + 8 * wt + i) * 64 + lane]);
-        GG_WAIT_LGKM0();
-    };
-    auto mma_range = [&](int i0, int i1) {
-#pragma unroll
-        for (int i = 0; i < 8; i++)
-            if (i >= i0 && i < i1 && i < my_blocks) {
-#pragma unroll
-                for (int j = 0; j < 4; j++)
-                    acc[i][j] =
-                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], bfr[i], acc[i][j], 0, 0, 0);
-            }
-    };
-    auto mma = [&]() { mma_range(0, 8); };
+    TileInfo cur, nxt;
+    if (!tile_at(slot, cur)) return;
+    bool has_next = tile_at(slot + wgs_per_xcd, nxt);
+    TileSrc scur, snxt;
+    gg_tile_src(a, cur, wave, scur);
+    if (has_next) gg_tile_src(a, nxt, wave, snxt); else snxt = scur;
 
-    const int KT = a.KS;
-    for (int j = 0; j < GG_NS && j < KT; j++) issue_stage(j);
-    gg_wait_batches((KT - 1) < (GG_NS - 1) ? (KT - 1) : (GG_NS - 1));
+    // look-ahead sources: reduction step j of the current tile, or j-KT of the next one
+    auto b_src = [&](int i, int j) -> const char* {
+        const u32x4_t* p = (j < KT) ? scur.b[i] + (size_t)j * 64 : snxt.b[i] + (size_t)(j - KT) * 64;
+        return (const char*)p + voff;
+    };
+    auto a_src = [&](int jr, int j) -> const u32x4_t* {
+        const u32x4_t* p = (j < KT) ? scur.a[jr] + (size_t)j * 64 : snxt.a[jr] + (size_t)(j - KT) * 64;
+        return (const u32x4_t*)((const char*)p + voff);
+    };
+    // g = running step count of this workgroup (never reset): LDS stage g % GG_NS
+    auto issue_b = [&](int i, int j, int gstage) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)b_src(i, j),
+            (__attribute__((address_space(3))) void*)(lds + ((gstage % GG_NS) * 16 + 4 * wave + i) * 64),
+            16, 0, 0);
+    };
+
+    f32x4_t acc[16][4];
+    u32x4_t areg[GG_PA][4];
+    bf16x8_t breg[16];
+
+    // ---- prologue of the first tile: request stages 0..NS-2 and A of steps 0..PA-2 ----
+    for (int j = 0; j < GG_NS - 1; j++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) issue_b(i, j, j);
+#pragma unroll
+    for (int s = 0; s < GG_PA - 1; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) areg[s][j] = *a_src(j, s);
+    GG_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
-    if (wt == 0) {
-        for (int k = 0; k < KT; k++) {
-            // slot 2k: read stage k (and refill the buffer stage k-1 has left)
-            if (k >= 1 && k + GG_NS - 1 < KT) issue_stage(k + GG_NS - 1);
-            read_frags(k);
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            // slot 2k+1: multiply stage k; before leaving, stage k+1 must have landed
-            mma();
-            __builtin_amdgcn_sched_barrier(0);
-            if (k + 1 < KT) gg_wait_batches((KT - 2 - k) < (GG_NS - 2) ? (KT - 2 - k) : (GG_NS - 2));
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    } else {
-        __builtin_amdgcn_s_barrier();  // slot 0: idle
-        for (int k = 0; k < KT; k++) {
-            // slot 2k+1: read stage k; before leaving, stage k+1 must have landed
-            read_frags(k);
-            if (k + 1 < KT) gg_wait_batches((KT - 2 - k) < (GG_NS - 2) ? (KT - 2 - k) : (GG_NS - 2));
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            // slot 2k+2: stage k's buffer is free: refill it, then multiply stage k
-            mma_range(0, 2);
-            if (k + GG_NS < KT) issue_stage(k + GG_NS);
-            mma_range(2, 8);
-            __builtin_amdgcn_sched_barrier(0);
-            if (k + 1 < KT) __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) breg[i] = __builtin_bit_cast(bf16x8_t, lds[i * 64 + lane]);
+    GG_WAIT_LGKM(0);
 
-    // ---- epilogue ----
-    const int t = lane & 15, fq = lane >> 4;  // token in block, feature quad
+    int g = 0;  // running step count
+    for (;;) {
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        if (i >= my_blocks) continue;
-        const int blk = blk0 + 8 * wt + i;  // block inside the segment
-        if (UP) {
-            // fragment rows 4*wn+j: j even = w1 rows, j odd = w3 rows of the same 16 columns.
+        for (int i = 0; i < 16; i++)
 #pragma unroll
-            for (int jj = 0; jj < 2; jj++) {
-                const f32x4_t av = acc[i][2 * jj], bv = acc[i][2 * jj + 1];
-                float hv[4];
+            for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        // the compiler cannot see the MFMAs below: cover the register write -> matrix read hazard
+        asm volatile("s_nop 7" ::: "memory");
+
+        // One reduction step.  Ac: weight fragments of this step; An: ring slot that
+        // receives the fragments of step k+GG_PA-1.  fast: every look-ahead lies inside
+        // the current tile, so there is nothing to decide (compile-time after inlining).
+        auto step = [&](int k, u32x4_t(&Ac)[4], u32x4_t(&An)[4], const bool fast) {
+            // do the look-ahead requests exist (in this tile or the next one)?
+            const bool la_b = fast || has_next || (k + GG_NS - 1 < KT);
+            const bool la_a = fast || has_next || (k + GG_PA - 1 < KT);
+            const bool more = fast || has_next || (k + 1 < KT);
+            // Stage k+1 and the weights of step k were requested >= 2 steps ago; requests
+            // retire in order, so at most the last two steps' worth may still be in flight.
+            // Once the stream has ended (last tile, no look-ahead) wait for everything.
+            if (la_b) GG_WAIT_VMCNT((GG_PA - 2) * GG_VMEM_PER_STEP);
+            else GG_WAIT_VMCNT(0);
+            if (more) __builtin_amdgcn_s_barrier();
+            const u32x4_t* pb = lds + ((g + 1) % GG_NS) * 16 * 64 + lane;
 #pragma unroll
-                for (int r = 0; r < 4; r++) hv[r] = av[r] / (1.0f + __expf(-av[r])) * bv[r];
-                // h column c = colblk*16 + 4*fq + r, colblk = global 16-column block
-                const int colblk = nt * (GG_FROWS / 2) + 2 * wn + jj;
-                const int ks_o = colblk >> 1;
-                const int lane_o = ((colblk & 1) * 2 + (fq >> 1)) * 16 + t;
-                uint2 pk;
-                pk.x = moe_pack_bf16x2(hv[0], hv[1]);
-                pk.y = moe_pack_bf16x2(hv[2], hv[3]);
-                unsigned char* dst = (unsigned char*)a.out +
-                                     (((size_t)(si.bbase + blk) * a.KS_out + ks_o) * 64 + lane_o) * 16 +
-                                     (fq & 1) * 8;
-                *(uint2*)dst = pk;
+            for (int i = 0; i < 16; i++) {
+                // one vector-memory request per 8 MFMAs, so that the requests of the four
+                // waves never queue up in front of the matrix instructions
+                if ((i & 1) == 0) {
+                    const int v = i >> 1;
+                    if (v < 4) {
+                        if (fast) {
+                            __builtin_amdgcn_global_load_lds(
+                                (const __attribute__((address_space(1))) void*)(
+                                    (const char*)(scur.b[v] + (size_t)(k + GG_NS - 1) * 64) + voff),
+                                (__attribute__((address_space(3))) void*)(
+                                    lds + (((g + GG_NS - 1) % GG_NS) * 16 + 4 * wave + v) * 64),
+                                16, 0, 0);
+                        } else if (la_b) {
+                            issue_b(v, k + GG_NS - 1, g + GG_NS - 1);
+                        }
+                    } else {
+                        if (fast)
+                            An[v - 4] = *(const u32x4_t*)((const char*)(scur.a[v - 4] +
+                                                          (size_t)(k + GG_PA - 1) * 64) + voff);
+                        else if (la_a)
+                            An[v - 4] = *a_src(v - 4, k + GG_PA - 1);
+                    }
+                    // LDS reads return in order: with at most 14 younger ones in flight,
+                    // breg[i] and breg[i+1] (refilled one step ago) have arrived
+                    GG_WAIT_LGKM(14);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
+                if (more) breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
             }
-        } else {
-            const int r_in_seg = blk * 16 + t;
-            if (r_in_seg < si.rows) {
-                float* row = (float*)a.out + (size_t)(si.row0 + r_in_seg) * a.C;
+            g++;
+        };
+        // steps whose look-aheads (k+GG_NS-1 at most) stay inside this tile: no conditions
+        const int k_fast = ((KT - GG_NS + 1) / GG_PA) * GG_PA;
+        int k = 0;
+        for (; k < k_fast; k += GG_PA) {
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    const int feat = (nt * GG_FROWS + 4 * wn + j) * 16 + 4 * fq;
-                    *(float4*)(row + feat) =
-                        make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            for (int u = 0; u < GG_PA; u++)
+                step(k + u, areg[u], areg[(u + GG_PA - 1) % GG_PA], true);
+        }
+        for (; k < KT; k += GG_PA) {
+#pragma unroll
+            for (int u = 0; u < GG_PA; u++)
+                step(k + u, areg[u], areg[(u + GG_PA - 1) % GG_PA], false);
+        }
+
+        // ---- epilogue of the current tile (the next tile's loads are in flight) ----
+        // the compiler cannot see the MFMAs: cover the matrix-core write -> read hazard
+        asm volatile("s_nop 15\n s_nop 15" ::: "memory");
+        const int t = lane & 15, fq = lane >> 4;  // token in block, feature quad
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            if (i >= cur.nblk) continue;
+            const int blk = cur.blk0 + i;  // block inside the segment
+            if (UP) {
+                // fragment rows 4*wave+j: j even = w1 rows, j odd = w3 rows of the same columns
+#pragma unroll
+                for (int jj = 0; jj < 2; jj++) {
+                    const f32x4_t av = acc[i][2 * jj], bv = acc[i][2 * jj + 1];
+                    float hv[4];
+#pragma unroll
+                    for (int r = 0; r < 4; r++) hv[r] = av[r] / (1.0f + __expf(-av[r])) * bv[r];
+                    const int colblk = cur.nt * (GG_FROWS / 2) + 2 * wave + jj;  // 16 h-columns
+                    const int ks_o = colblk >> 1;
+                    const int lane_o = ((colblk & 1) * 2 + (fq >> 1)) * 16 + t;
+                    uint2 pk;
+                    pk.x = moe_pack_bf16x2(hv[0], hv[1]);
+                    pk.y = moe_pack_bf16x2(hv[2], hv[3]);
+                    unsigned char* dst =
+                        (unsigned char*)a.out +
+                        (((size_t)(cur.si.bbase + blk) * a.KS_out + ks_o) * 64 + lane_o) * 16 +
+                        (fq & 1) * 8;
+                    *(uint2*)dst = pk;
+                }
+            } else {
+                const int r_in_seg = blk * 16 + t;
+                if (r_in_seg < cur.si.rows) {
+                    float* row = (float*)a.out + (size_t)(cur.si.row0 + r_in_seg) * a.C;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        const int feat = (cur.nt * GG_FROWS + 4 * wave + j) * 16 + 4 * fq;
+                        *(float4*)(row + feat) =
+                            make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+                    }
                 }
             }
         }
+        if (!has_next) break;
+        // advance: next becomes current; look one tile further ahead
+        slot += wgs_per_xcd;
+        cur = nxt;
+        scur = snxt;
+        has_next = tile_at(slot + wgs_per_xcd, nxt);
+        if (has_next) gg_tile_src(a, nxt, wave, snxt);
+        GG_WAIT_LGKM(0);  // scalar loads of the decode must not sit in the LDS read counter
     }
 }
 
@@ -394,13 +405,14 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
                            const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
     const int d = W->d, f = W->f, E = W->E;
     // up tile = 16 fragment rows = 8 column blocks x (w1,w3): f % 128 == 0;
-    // down tile = 256 features: d % 256 == 0; stages of 64: d % 64 == 0, f % 64 == 0.
+    // down tile = 256 features: d % 256 == 0; both give reductions of >= 8 steps, step
+    // counts that are multiples of 4.
     if (f % 128 != 0 || d % 256 != 0) return MOE_ERR_UNSUPPORTED;
     const size_t nb = gg_max_blocks(N, E);
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
-    const int max_tiles = N / (16 * GG_TILE_BLOCKS) + E;
-    const size_t lds_bytes = GG_NS * 32 * MOE_FRAG_BYTES;
+    const size_t lds_bytes = GG_NS * 16 * MOE_FRAG_BYTES;
+    const unsigned pgrid = (unsigned)((moe_num_cus() + 7) / 8 * 8);  // persistent: one per CU
 
     static bool attr_set = false;
     if (!attr_set) {
@@ -429,8 +441,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.NT = up.FR / GG_FROWS;
     up.KS_out = f / 32;
     up.C = 0;
-    hipLaunchKernelGGL(gg_gemm_kernel<true>, dim3((unsigned)((up.NT * max_tiles + 7) / 8 * 8)), dim3(GG_THREADS),
-                       lds_bytes, s, up);
+    hipLaunchKernelGGL(gg_gemm_kernel<true>, dim3(pgrid), dim3(GG_THREADS), lds_bytes, s, up);
     moe_record_mid_event(s);
 
     GroupedArgs dn;
@@ -444,7 +455,6 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.NT = dn.FR / GG_FROWS;
     dn.KS_out = 0;
     dn.C = d;
-    hipLaunchKernelGGL(gg_gemm_kernel<false>, dim3((unsigned)((dn.NT * max_tiles + 7) / 8 * 8)), dim3(GG_THREADS),
-                       lds_bytes, s, dn);
+    hipLaunchKernelGGL(gg_gemm_kernel<false>, dim3(pgrid), dim3(GG_THREADS), lds_bytes, s, dn);
     return moe_launch_status();
 }
