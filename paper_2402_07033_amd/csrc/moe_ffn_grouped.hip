@@ -290,7 +290,12 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             // Once the stream has ended (last tile, no look-ahead) wait for everything.
             if (la_b) GG_WAIT_VMCNT((GG_PA - 2) * GG_VMEM_PER_STEP);
             else GG_WAIT_VMCNT(0);
-            if (more) __builtin_amdgcn_s_barrier();
+            // One barrier per TWO steps: at an even step every wave has waited for all its
+            // requests older than two steps, which covers its shares of stages k+1 and k+2
+            // (requested GG_NS-2 and GG_NS-3 steps ago), so both are published here; and the
+            // buffers refilled during steps k and k+1 (stages k-1 and k) were last read
+            // before this barrier.
+            if (more && (k & 1) == 0) __builtin_amdgcn_s_barrier();
             const u32x4_t* pb = lds + ((g + 1) % GG_NS) * 16 * 64 + lane;
 #pragma unroll
             for (int i = 0; i < 16; i++) {
@@ -408,6 +413,9 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     // down tile = 256 features: d % 256 == 0; both give reductions of >= 8 steps, step
     // counts that are multiples of 4.
     if (f % 128 != 0 || d % 256 != 0) return MOE_ERR_UNSUPPORTED;
+    // the step loop is unrolled by the register-ring depth and looks GG_NS-1 steps ahead
+    if ((d / 32) % GG_PA != 0 || (f / 32) % GG_PA != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
+        return MOE_ERR_UNSUPPORTED;
     const size_t nb = gg_max_blocks(N, E);
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
