@@ -28,6 +28,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by the 1 GiB copy calibration; see the summaries under profiles/).  Static figures
+# from those profile runs, not measured by this script.
+TRAFFIC_BYTES = {
+    "decode_t1": 470.5e6,       # profiles/stream_kernels_decode_t1.txt
+}
+
 WORKLOADS = {
     # name: (T, x dtype, zipf skew of the router logits, bound)
     "decode_t1": dict(T=1, x_bf16=False, zipf=None, bound="hbm"),
@@ -258,7 +265,7 @@ def run_stack(args, torch, moe, wl):
         n_tok = min(T, 4)
         xs = x0[:n_tok].cpu().numpy().astype(np.float64)
         reps, t_used = 0, 0.0
-        while t_used < 10.0 and reps < 8:
+        while t_used < 12.0 and reps < 400:
             t0 = time.perf_counter()
             orc.stack(xs, [(host_gate.numpy(), w1, w3, w2)], K)
             t_used += time.perf_counter() - t0
@@ -271,6 +278,29 @@ def run_stack(args, torch, moe, wl):
     print(json.dumps(result))
 
 
+def mfma_ceiling(torch, moe):
+    """Sustained matrix-core rate of this board for constant and for random bf16 operands
+    (register-resident MFMA loop, no memory traffic): context for the MFMA roofline."""
+    events = HipEvents()
+    stream = torch.cuda.current_stream().cuda_stream
+    out = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    for name, ops in (("constant", torch.full((32768,), 0.5, dtype=torch.bfloat16, device="cuda")),
+                      ("random_normal", torch.randn(32768, generator=g, device="cuda")
+                       .to(torch.bfloat16))):
+        moe.moe_mfma_rate_probe(ops, 200, out)
+        torch.cuda.synchronize()
+        e0, e1 = events.create(), events.create()
+        events.record(e0, stream)
+        flops = moe.moe_mfma_rate_probe(ops, 4000, out)
+        events.record(e1, stream)
+        ms = events.elapsed_ms(e0, e1)
+        res[name] = flops / (ms * 1e-3) / 1e12
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -279,6 +309,8 @@ def main():
     ap.add_argument("--workload", default="decode_t1", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="only measure the sustained matrix-core rate of this board")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size reference dispatch "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -293,6 +325,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.mfma_ceiling:
+        print(json.dumps({"mfma_sustained_TFLOPs_bf16_16x16x32": mfma_ceiling(torch, moe),
+                          "published_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS}))
+        return
     wl = WORKLOADS[args.workload]
     T = wl["T"]
     if "layers" in wl:
@@ -365,7 +401,7 @@ def main():
         up_bytes = n_active * 2 * D * F * 2
         achieved = up_bytes / (up_ms * 1e-3) / 1e9
         roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=achieved / HBM_PEAK_GBS, traffic=None,
+                        frac=achieved / HBM_PEAK_GBS, traffic=TRAFFIC_BYTES.get(args.workload),
                         kernel="stream_kernel<KSW=16,NMAT=2> (x.w1, x.w3, silu*mul)",
                         kernel_ms=up_ms, second_projection_ms=dn_ms,
                         second_projection_GBs=n_active * D * F * 2 / (dn_ms * 1e-3) / 1e9,
@@ -374,7 +410,8 @@ def main():
         up_flops = T * K * 2 * 2 * D * F  # real rows only
         achieved = up_flops / (up_ms * 1e-3) / 1e12
         roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
-                        unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                        unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS,
+                        traffic=TRAFFIC_BYTES.get(args.workload),
                         kernel="gg_pack + gg_gemm_kernel<UP> (x.w1, x.w3, silu*mul)",
                         kernel_ms=up_ms, second_projection_ms=dn_ms,
                         second_projection_TFLOPs=T * K * 2 * D * F / (dn_ms * 1e-3) / 1e12,

@@ -167,6 +167,20 @@ int moe_residual_add(float* x, const float* y, int T, int d, void* stream);
  */
 int moe_set_ffn_mid_event(void* hip_event);
 
+/*
+ * Measurement probe (not part of the layer): runs `iters` rounds of a
+ * register-resident v_mfma_f32_16x16x32_bf16 loop with no memory traffic on every
+ * CU and reports the flop count, so that a caller timing it with events learns the
+ * matrix-core rate this board sustains for the given operand bits (the published
+ * peak assumes the maximum clock; the board lowers it under load, more so for
+ * random operands than for constant ones).
+ *   operands  64 KiB of bf16 bit patterns (DEVICE), 16-byte aligned
+ *   out       2 * CUs * 256 floats of scratch (DEVICE; 512 * 256 floats suffice)
+ *   flops     HOST pointer that receives the flop count of the launch (may be NULL)
+ */
+int moe_mfma_rate_probe(const void* operands, int iters, float* out, double* flops,
+                        void* stream);
+
 #ifdef __cplusplus
 }
 #endif

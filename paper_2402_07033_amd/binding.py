@@ -19,7 +19,8 @@ _lib = None
 EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
-           "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event")
+           "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
+           "moe_mfma_rate_probe")
 
 
 class MoeError(RuntimeError):
@@ -60,9 +61,12 @@ def lib():
         L.moe_residual_add.argtypes = [vp, vp, i32, i32, vp]
         L.moe_set_ffn_mid_event.argtypes = [vp]
         L.moe_set_ffn_mid_event.restype = C.c_int
+        L.moe_mfma_rate_probe.argtypes = [vp, i32, vp, C.POINTER(C.c_double), vp]
+        L.moe_mfma_rate_probe.restype = C.c_int
         for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
                   "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
-                  "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event"):
+                  "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
+           "moe_mfma_rate_probe"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -250,6 +254,14 @@ def moe_set_ffn_mid_event(hip_event: Optional[int]):
     """hipEvent_t handle (int) recorded between the two projections, or None."""
     _check(lib().moe_set_ffn_mid_event(C.c_void_p(hip_event) if hip_event else None),
            "moe_set_ffn_mid_event")
+
+
+def moe_mfma_rate_probe(operands: torch.Tensor, iters: int, out: torch.Tensor, stream=None) -> float:
+    """Launch the matrix-core rate probe; returns the flop count of the launch."""
+    flops = C.c_double()
+    _check(lib().moe_mfma_rate_probe(_ptr(operands), iters, _ptr(out), C.byref(flops),
+                                     _stream(stream)), "moe_mfma_rate_probe")
+    return float(flops.value)
 
 
 def moe_layer(W: PackedWeights, x: torch.Tensor, logits: torch.Tensor, k: int,

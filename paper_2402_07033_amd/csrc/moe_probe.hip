@@ -1,0 +1,51 @@
+// Measurement probe: a register-resident MFMA loop with no memory traffic in
+// it.  It answers one question for the roofline discussion: what rate do the
+// matrix cores of THIS board sustain on v_mfma_f32_16x16x32_bf16 when the
+// operands are realistic (random) rather than constant?  The published peak
+// assumes the maximum clock; under a matrix-core load the board lowers its
+// clock, and more so when the operand bits toggle.
+#include "moe_internal.h"
+
+// 4 waves per workgroup, 16 accumulators per wave, operands cycle through 8
+// register sets loaded once from `operands` (64 KiB of bf16 bit patterns).
+__global__ __launch_bounds__(256) void mfma_rate_kernel(const u32x4_t* __restrict__ operands,
+                                                        float* __restrict__ out, int iters) {
+    const int lane = threadIdx.x & 63;
+    u32x4_t a[8][4], b[8][4];
+#pragma unroll
+    for (int s = 0; s < 8; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            a[s][j] = operands[((blockIdx.x * 7 + s * 4 + j) & 31) * 64 + lane];
+            b[s][j] = operands[((blockIdx.x * 13 + s * 4 + j + 32) & 63) * 64 + lane];
+        }
+    f32x4_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int s = 0; s < 8; s++)
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8_t, a[s][j]), __builtin_bit_cast(bf16x8_t, b[s][i]),
+                        acc[i * 4 + j], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i++) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+extern "C" int moe_mfma_rate_probe(const void* operands, int iters, float* out, double* flops,
+                                   void* stream) {
+    if (!operands || !out || iters < 1 || iters > (1 << 20) || !moe_aligned16(operands))
+        return MOE_ERR_INVALID_ARG;
+    const unsigned blocks = (unsigned)(2 * moe_num_cus());
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const u32x4_t*)operands, out, iters);
+    if (flops) *flops = (double)blocks * 4.0 * iters * 8.0 * 16.0 * 16384.0;
+    return moe_launch_status();
+}
