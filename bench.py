@@ -33,6 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # from those profile runs, not measured by this script.
 TRAFFIC_BYTES = {
     "decode_t1": 470.5e6,       # profiles/stream_kernels_decode_t1.txt
+    "prefill_t4096": 4.82e9,    # profiles/grouped_gemm_prefill_t4096.txt (fetch 4.58 GB + write 0.24 GB)
 }
 
 WORKLOADS = {
@@ -122,8 +123,9 @@ def make_inputs(torch, moe, wl, n_inputs, seed):
 class Step:
     """Preallocated buffers + the four C-ABI calls of one step."""
 
-    def __init__(self, torch, moe, T, x_dtype):
+    def __init__(self, torch, moe, T, x_dtype, fused_gate=False):
         N = T * K
+        self.fused_gate = fused_gate and T <= 16 and x_dtype == torch.float32
         i32 = dict(dtype=torch.int32, device="cuda")
         f32 = dict(dtype=torch.float32, device="cuda")
         self.moe = moe
@@ -139,8 +141,13 @@ class Step:
 
     def run(self, W, x, logits, ev=None, events=None, stream=0):
         moe = self.moe
-        moe.moe_route(logits, K, self.idx, self.w)
-        counts, offsets, perm, inv_perm, xg = moe.moe_permute(self.idx, E, x, out=self.perm_out)
+        if self.fused_gate:
+            moe.moe_route_permute(logits, K, x, self.idx, self.w, self.perm_out)
+            counts, offsets, perm, inv_perm, xg = self.perm_out
+        else:
+            moe.moe_route(logits, K, self.idx, self.w)
+            counts, offsets, perm, inv_perm, xg = moe.moe_permute(self.idx, E, x,
+                                                                  out=self.perm_out)
         if ev is not None:
             events.record(ev[0], stream)
         moe.moe_expert_ffn(W, xg, offsets, workspace=self.ws, yg=self.yg)
@@ -309,6 +316,9 @@ def main():
     ap.add_argument("--workload", default="decode_t1", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-gate", action="store_true",
+                    help="decode-sized workloads: use the one-launch moe_route_permute instead "
+                         "of moe_route + moe_permute (same outputs)")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="only measure the sustained matrix-core rate of this board")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -348,7 +358,7 @@ def main():
         sets.append(W)
     torch.cuda.empty_cache()
     xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
-    step = Step(torch, moe, T, xs[0].dtype)
+    step = Step(torch, moe, T, xs[0].dtype, fused_gate=args.fused_gate)
     stream = torch.cuda.current_stream().cuda_stream
     events = HipEvents()
 
@@ -426,7 +436,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "d_model": D, "d_ff": F, "experts": E,
                    "top_k": K, "weight_sets_rotated": n_layers, "inputs_rotated": n_inputs,
-                   "counts_first_input": counts_all[0]},
+                   "counts_first_input": counts_all[0],
+                   "calls_per_step": ("moe_route_permute, moe_expert_ffn, moe_combine"
+                                      if step.fused_gate else
+                                      "moe_route, moe_permute, moe_expert_ffn, moe_combine")},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

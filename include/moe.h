@@ -159,6 +159,28 @@ int moe_router_logits(const float* h, const float* w_gate, int T, int d, int E, 
 int moe_residual_add(float* x, const float* y, int T, int d, void* stream);
 
 /*
+ * Fused front ends for decode-sized batches: the same results as the separate calls, in
+ * one launch each (at T = 1 the launch latency of every small kernel is a few percent of
+ * the layer).  Both return MOE_ERR_UNSUPPORTED outside their domain; callers then use the
+ * separate calls.
+ *   moe_route_permute:      moe_route + moe_permute (fp32 x).  T <= 16, E <= 16.
+ *   moe_norm_route_permute: moe_rmsnorm + moe_router_logits + moe_route + moe_permute of
+ *                           the normalised rows.  T <= 4, E <= 16.  h [T,d] and logits
+ *                           [T,E] are outputs; logits = (x . w_gate) / rms(x) in fp32.
+ *   moe_combine_residual:   x[t,:] += sum_j weights[t,j] * yg[inv_perm[t*k+j], :]
+ *                           (moe_combine + moe_residual_add), any T.
+ */
+int moe_route_permute(const float* logits, int T, int E, int k, const float* x, int d,
+                      int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
+                      int32_t* perm, int32_t* inv_perm, float* xg, void* stream);
+int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, int E, int k,
+                           float eps, float* h, float* logits, int32_t* idx, float* weights,
+                           int32_t* counts, int32_t* offsets, int32_t* perm,
+                           int32_t* inv_perm, float* xg, void* stream);
+int moe_combine_residual(const float* yg, const int32_t* inv_perm, const float* weights, int T,
+                         int k, int d, float* x, void* stream);
+
+/*
  * Measurement hook: when `hip_event` (a hipEvent_t as void*, HOST handle) is
  * non-NULL, every following moe_expert_ffn call records it on its stream
  * between the first projection (x.w1, x.w3, silu*mul) and the second (h.w2),

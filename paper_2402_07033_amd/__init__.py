@@ -5,7 +5,8 @@ Every step runs in hand-written HIP kernels; PyTorch only provides device
 memory and streams.  There is no CPU fallback: importing the binding's
 functions without the built library raises.
 """
-from .binding import (StackBuffers, moe_mfma_rate_probe, moe_stack_forward, MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_STREAM,
+from .binding import (StackBuffers, moe_route_permute, moe_norm_route_permute,
+                      moe_combine_residual, moe_mfma_rate_probe, moe_stack_forward, MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_STREAM,
                       MoeError, PackedWeights, lib, lib_path, moe_combine, moe_expert_ffn,
                       moe_expert_ffn_workspace, moe_layer, moe_permute, moe_residual_add,
                       moe_rmsnorm, moe_route, moe_router_logits, moe_set_ffn_mid_event,
@@ -13,7 +14,8 @@ from .binding import (StackBuffers, moe_mfma_rate_probe, moe_stack_forward, MOE_
                       moe_weights_free, moe_weights_pack)
 
 __all__ = [
-    "StackBuffers", "moe_stack_forward", "moe_mfma_rate_probe",
+    "StackBuffers", "moe_stack_forward", "moe_route_permute", "moe_norm_route_permute",
+    "moe_combine_residual", "moe_mfma_rate_probe",
     "MOE_BF16", "MOE_F32", "MOE_FFN_AUTO", "MOE_FFN_GROUPED", "MOE_FFN_STREAM", "MoeError",
     "PackedWeights", "lib", "lib_path", "moe_combine", "moe_expert_ffn",
     "moe_expert_ffn_workspace", "moe_layer", "moe_permute", "moe_residual_add", "moe_rmsnorm",

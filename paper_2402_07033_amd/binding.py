@@ -20,7 +20,8 @@ EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
            "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
-           "moe_mfma_rate_probe")
+           "moe_mfma_rate_probe", "moe_route_permute", "moe_norm_route_permute",
+           "moe_combine_residual")
 
 
 class MoeError(RuntimeError):
@@ -63,10 +64,17 @@ def lib():
         L.moe_set_ffn_mid_event.restype = C.c_int
         L.moe_mfma_rate_probe.argtypes = [vp, i32, vp, C.POINTER(C.c_double), vp]
         L.moe_mfma_rate_probe.restype = C.c_int
+        L.moe_route_permute.argtypes = [vp, i32, i32, i32, vp, i32] + [vp] * 8
+        L.moe_route_permute.restype = C.c_int
+        L.moe_norm_route_permute.argtypes = [vp, vp, i32, i32, i32, i32, f32] + [vp] * 10
+        L.moe_norm_route_permute.restype = C.c_int
+        L.moe_combine_residual.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+        L.moe_combine_residual.restype = C.c_int
         for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
                   "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
                   "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
-           "moe_mfma_rate_probe"):
+           "moe_mfma_rate_probe", "moe_route_permute", "moe_norm_route_permute",
+           "moe_combine_residual"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -275,6 +283,39 @@ def moe_layer(W: PackedWeights, x: torch.Tensor, logits: torch.Tensor, k: int,
                 xg=xg, yg=yg, y=y)
 
 
+def moe_route_permute(logits: torch.Tensor, k: int, x: torch.Tensor, idx, weights, out,
+                      stream=None):
+    """Fused moe_route + moe_permute for T <= 16 (fp32 x); outputs as in the two calls."""
+    T, E = logits.shape
+    counts, offsets, perm, inv_perm, xg = out
+    _check(lib().moe_route_permute(_ptr(logits), T, E, k, _ptr(x), x.shape[1], _ptr(idx),
+                                   _ptr(weights), _ptr(counts), _ptr(offsets), _ptr(perm),
+                                   _ptr(inv_perm), _ptr(xg), _stream(stream)), "moe_route_permute")
+    return idx, weights, out
+
+
+def moe_norm_route_permute(x: torch.Tensor, w_gate: torch.Tensor, k: int, eps: float, h, logits,
+                           idx, weights, out, stream=None):
+    """Fused rmsnorm + router logits + route + permute for T <= 4."""
+    T, d = x.shape
+    E = w_gate.shape[1]
+    counts, offsets, perm, inv_perm, xg = out
+    _check(lib().moe_norm_route_permute(_ptr(x), _ptr(w_gate), T, d, E, k, eps, _ptr(h),
+                                        _ptr(logits), _ptr(idx), _ptr(weights), _ptr(counts),
+                                        _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(xg),
+                                        _stream(stream)), "moe_norm_route_permute")
+    return out
+
+
+def moe_combine_residual(yg: torch.Tensor, inv_perm: torch.Tensor, weights: torch.Tensor,
+                         x: torch.Tensor, stream=None):
+    """x[t] += sum_j weights[t,j] * yg[inv_perm[t*k+j]] in one launch."""
+    T, k = weights.shape
+    _check(lib().moe_combine_residual(_ptr(yg), _ptr(inv_perm), _ptr(weights), T, k, yg.shape[1],
+                                      _ptr(x), _stream(stream)), "moe_combine_residual")
+    return x
+
+
 class StackBuffers:
     """Preallocated device buffers for moe_stack_forward (one layer's worth, reused)."""
 
@@ -295,23 +336,32 @@ class StackBuffers:
 
 
 def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=None,
-                      logits_out=None, idx_out=None, on_layer=None, stream=None):
+                      logits_out=None, idx_out=None, on_layer=None, fused: bool = True,
+                      stream=None):
     """The layer-stack workload: for every (PackedWeights, w_gate) in `layers`
         h = rmsnorm(x); logits = h . w_gate; y = moe_layer(h, logits); x += y
     x (fp32 [T,d]) is updated in place.  logits_out / idx_out, when given, are lists
     that receive a copy of every layer's router logits / expert indices.  on_layer(l)
-    is called before each layer's expert FFN is enqueued (measurement hook)."""
+    is called before each layer's expert FFN is enqueued (measurement hook).  fused=True
+    uses the one-launch front end (T <= 4) and combine+residual; fused=False the separate
+    calls."""
     _dev(x, torch.float32, "x")
     T, d = x.shape
     W0 = layers[0][0]
     if bufs is None:
         bufs = StackBuffers(T, W0.E, k, d, W0.f, x.device)
+    fused_gate = fused and T <= 4 and W0.E <= 16
     for li, (W, w_gate) in enumerate(layers):
-        moe_rmsnorm(x, eps, bufs.h, stream=stream)
-        moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
-        moe_route(bufs.logits, k, bufs.idx, bufs.w, stream=stream)
-        _, offsets, _, inv_perm, xg = moe_permute(bufs.idx, W.E, bufs.h, out=bufs.perm_out,
-                                                  stream=stream)
+        if fused_gate:
+            moe_norm_route_permute(x, w_gate, k, eps, bufs.h, bufs.logits, bufs.idx, bufs.w,
+                                   bufs.perm_out, stream=stream)
+            _, offsets, _, inv_perm, xg = bufs.perm_out
+        else:
+            moe_rmsnorm(x, eps, bufs.h, stream=stream)
+            moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
+            moe_route(bufs.logits, k, bufs.idx, bufs.w, stream=stream)
+            _, offsets, _, inv_perm, xg = moe_permute(bufs.idx, W.E, bufs.h, out=bufs.perm_out,
+                                                      stream=stream)
         if logits_out is not None:
             logits_out.append(bufs.logits.clone())
         if idx_out is not None:
@@ -319,6 +369,9 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
         if on_layer is not None:
             on_layer(li)
         moe_expert_ffn(W, xg, offsets, workspace=bufs.ws, yg=bufs.yg, stream=stream)
-        moe_combine(bufs.yg, inv_perm, bufs.w, bufs.y, stream=stream)
-        moe_residual_add(x, bufs.y, stream=stream)
+        if fused:
+            moe_combine_residual(bufs.yg, inv_perm, bufs.w, x, stream=stream)
+        else:
+            moe_combine(bufs.yg, inv_perm, bufs.w, bufs.y, stream=stream)
+            moe_residual_add(x, bufs.y, stream=stream)
     return x

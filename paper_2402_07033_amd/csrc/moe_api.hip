@@ -152,4 +152,40 @@ int moe_residual_add(float* x, const float* y, int T, int d, void* stream) {
     return moe_residual_add_launch(x, y, T, d, (hipStream_t)stream);
 }
 
+int moe_route_permute(const float* logits, int T, int E, int k, const float* x, int d,
+                      int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
+                      int32_t* perm, int32_t* inv_perm, float* xg, void* stream) {
+    if (!tek_ok(T, E, k) || !dims_ok(d)) return MOE_ERR_INVALID_ARG;
+    if (!logits || !x || !idx || !weights || !counts || !offsets || !perm || !inv_perm || !xg)
+        return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(x) || !moe_aligned16(xg)) return MOE_ERR_INVALID_ARG;
+    if (T < 1 || T > 16 || E > 16) return MOE_ERR_UNSUPPORTED;
+    return moe_gate_small_launch(false, x, nullptr, logits, T, d, E, k, 0.f, nullptr, nullptr, idx,
+                                 weights, counts, offsets, perm, inv_perm, xg, (hipStream_t)stream);
+}
+
+int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, int E, int k,
+                           float eps, float* h, float* logits, int32_t* idx, float* weights,
+                           int32_t* counts, int32_t* offsets, int32_t* perm,
+                           int32_t* inv_perm, float* xg, void* stream) {
+    if (!tek_ok(T, E, k) || !dims_ok(d) || !(eps >= 0.f)) return MOE_ERR_INVALID_ARG;
+    if (!x || !w_gate || !h || !logits || !idx || !weights || !counts || !offsets || !perm ||
+        !inv_perm || !xg)
+        return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(x) || !moe_aligned16(xg) || !moe_aligned16(h)) return MOE_ERR_INVALID_ARG;
+    if (T < 1 || T > 4 || E > 16) return MOE_ERR_UNSUPPORTED;
+    return moe_gate_small_launch(true, x, w_gate, nullptr, T, d, E, k, eps, h, logits, idx, weights,
+                                 counts, offsets, perm, inv_perm, xg, (hipStream_t)stream);
+}
+
+int moe_combine_residual(const float* yg, const int32_t* inv_perm, const float* weights, int T,
+                         int k, int d, float* x, void* stream) {
+    if (T < 0 || k < 1 || k > MOE_MAX_K || (long long)T * k >= MOE_MAX_N || !dims_ok(d))
+        return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!yg || !inv_perm || !weights || !x) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(yg) || !moe_aligned16(x)) return MOE_ERR_INVALID_ARG;
+    return moe_combine_residual_launch(yg, inv_perm, weights, T, k, d, x, (hipStream_t)stream);
+}
+
 }  // extern "C"

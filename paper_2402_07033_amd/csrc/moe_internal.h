@@ -107,3 +107,9 @@ int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t 
 int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E, int d, int f,
                           moe_dtype_t w_dtype, moe_weights** out, hipStream_t s);
 int moe_weights_free_impl(moe_weights* W);
+int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const float* logits_in,
+                          int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
+                          int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
+                          int32_t* perm, int32_t* inv_perm, float* xg, hipStream_t s);
+int moe_combine_residual_launch(const float* yg, const int32_t* inv_perm, const float* weights, int T,
+                                int k, int d, float* x, hipStream_t s);

@@ -353,3 +353,234 @@ int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t 
                        (const float4*)y, n4);
     return moe_launch_status();
 }
+
+// --------------------------------------------- fused gate for decode-sized T ----
+// One launch for the whole front end of a decode step (T <= 16 tokens): optional
+// RMS normalisation + router logits, top-k routing, per-expert batching and the
+// row gather.  Every workgroup recomputes the (tiny) routing state in LDS;
+// workgroup 0 writes the index outputs; the workgroups share the row gather.
+#define GATE_MAX_T 16       // tokens the fused gate handles
+#define GATE_NORM_MAX_T 4   // ... when it also normalises and computes the router logits
+#define GATE_MAX_E 16
+
+template <bool NORM>
+__global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
+    const float* __restrict__ x, const float* __restrict__ w_gate, const float* __restrict__ logits_in,
+    int T, int d, int E, int k, float eps, float* __restrict__ h_out, float* __restrict__ logits_out,
+    int32_t* __restrict__ idx, float* __restrict__ weights, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+    float* __restrict__ xg) {
+    __shared__ int s_cnt[MOE_MAX_E];
+    __shared__ int s_off[MOE_MAX_E + 1];
+    __shared__ int s_wave[PERM_WAVES * MOE_MAX_E];
+    __shared__ int s_pos[GATE_MAX_T * MOE_MAX_K];
+    __shared__ int s_idx[GATE_MAX_T * MOE_MAX_K];
+    __shared__ float s_logits[GATE_MAX_T * GATE_MAX_E];
+    __shared__ float s_inv[GATE_MAX_T];
+    __shared__ float s_part[PERM_WAVES][GATE_NORM_MAX_T * (GATE_MAX_E + 1)];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool writer = (blockIdx.x == 0);
+
+    if (NORM) {
+        // T <= GATE_NORM_MAX_T here.  Per thread: rows r = tid, tid+1024, ...; partial sums
+        // of x^2 and of x * w_gate[:, e] for every token, reduced over the workgroup.
+        float ss[GATE_NORM_MAX_T], acc[GATE_NORM_MAX_T][GATE_MAX_E];
+#pragma unroll
+        for (int t = 0; t < GATE_NORM_MAX_T; t++) {
+            ss[t] = 0.f;
+#pragma unroll
+            for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = 0.f;
+        }
+        for (int r = tid; r < d; r += PERM_THREADS) {
+            float wr[GATE_MAX_E];
+#pragma unroll
+            for (int e = 0; e < GATE_MAX_E; e++) wr[e] = (e < E) ? w_gate[(size_t)r * E + e] : 0.f;
+#pragma unroll
+            for (int t = 0; t < GATE_NORM_MAX_T; t++) {
+                if (t < T) {
+                    const float xv = x[(size_t)t * d + r];
+                    ss[t] = fmaf(xv, xv, ss[t]);
+#pragma unroll
+                    for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = fmaf(xv, wr[e], acc[t][e]);
+                }
+            }
+        }
+        // wave reduce, then across the 16 waves through LDS
+#pragma unroll
+        for (int t = 0; t < GATE_NORM_MAX_T; t++) {
+            if (t < T) {
+#pragma unroll
+                for (int m = 32; m >= 1; m >>= 1) ss[t] += __shfl_xor(ss[t], m, 64);
+#pragma unroll
+                for (int e = 0; e < GATE_MAX_E; e++) {
+                    if (e < E) {
+#pragma unroll
+                        for (int m = 32; m >= 1; m >>= 1) acc[t][e] += __shfl_xor(acc[t][e], m, 64);
+                    }
+                }
+                if (lane == 0) {
+                    s_part[wave][t * (GATE_MAX_E + 1) + GATE_MAX_E] = ss[t];
+#pragma unroll
+                    for (int e = 0; e < GATE_MAX_E; e++)
+                        if (e < E) s_part[wave][t * (GATE_MAX_E + 1) + e] = acc[t][e];
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < T * (GATE_MAX_E + 1)) {
+            const int t = tid / (GATE_MAX_E + 1), e = tid % (GATE_MAX_E + 1);
+            if (e == GATE_MAX_E || e < E) {
+                float v = 0.f;
+                for (int w = 0; w < PERM_WAVES; w++) v += s_part[w][t * (GATE_MAX_E + 1) + e];
+                if (e == GATE_MAX_E) s_inv[t] = 1.0f / sqrtf(v / (float)d + eps);
+                else s_logits[t * GATE_MAX_E + e] = v;
+            }
+        }
+        __syncthreads();
+        // logits of the normalised rows: (x . w) * inv
+        if (tid < T * GATE_MAX_E) {
+            const int t = tid / GATE_MAX_E, e = tid % GATE_MAX_E;
+            if (e < E) {
+                const float v = s_logits[tid] * s_inv[t];
+                s_logits[tid] = v;
+                if (writer) logits_out[(size_t)t * E + e] = v;
+            }
+        }
+        __syncthreads();
+    } else {
+        if (tid < T * GATE_MAX_E) {
+            const int t = tid / GATE_MAX_E, e = tid % GATE_MAX_E;
+            if (e < E) s_logits[tid] = logits_in[(size_t)t * E + e];
+        }
+        __syncthreads();
+    }
+
+    // ---- top-k routing: 16 lanes per token (E <= 16), same contest as route_kernel ----
+    {
+        const int t = tid / GATE_MAX_E, gl = tid % GATE_MAX_E;
+        const bool live = (t < T);
+        float v = -INFINITY;
+        int e = 0x7fffffff;
+        if (live && gl < E) {
+            v = s_logits[t * GATE_MAX_E + gl];
+            e = gl;
+        }
+        float my_v = 0.f, top_v = 0.f;
+        int my_i = 0;
+        for (int j = 0; j < k; j++) {
+            float bv = v;
+            int be = e;
+#pragma unroll
+            for (int m = 1; m < GATE_MAX_E; m <<= 1) {
+                const float ov = __shfl_xor(bv, m, 64);
+                const int oe = __shfl_xor(be, m, 64);
+                if (ov > bv || (ov == bv && oe < be)) {
+                    bv = ov;
+                    be = oe;
+                }
+            }
+            if (j == 0) top_v = bv;
+            if (gl == j) {
+                my_v = bv;
+                my_i = be;
+            }
+            if (e == be) {
+                v = -INFINITY;
+                e = 0x7fffffff;
+            }
+        }
+        const float u = (gl < k) ? expf(my_v - top_v) : 0.f;
+        float s = u;
+#pragma unroll
+        for (int m = 1; m < GATE_MAX_E; m <<= 1) s += __shfl_xor(s, m, 64);
+        if (live && gl < k) {
+            s_idx[t * k + gl] = my_i;
+            if (writer) {
+                idx[(size_t)t * k + gl] = my_i;
+                weights[(size_t)t * k + gl] = u / s;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- per-expert batching on the LDS copy of idx, then the row gather ----
+    const int N = T * k;
+    permute_indices(s_idx, N, E, counts, offsets, perm, inv_perm, writer, s_cnt, s_off, s_wave,
+                    s_pos);
+    __syncthreads();
+    const int row_chunks = d / 4;
+    for (int p = blockIdx.x; p < N; p += gridDim.x) {
+        const int t = p / k;
+        const float4* src = (const float4*)(x + (size_t)t * d);
+        float4* dst = (float4*)(xg + (size_t)s_pos[p] * d);
+        const float sc = NORM ? s_inv[t] : 1.0f;
+        for (int c = tid; c < row_chunks; c += PERM_THREADS) {
+            float4 v = src[c];
+            if (NORM) {
+                v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+            }
+            dst[c] = v;
+        }
+    }
+    if (NORM && writer) {
+        for (int t = 0; t < T; t++) {
+            const float sc = s_inv[t];
+            for (int r = tid; r < d; r += PERM_THREADS)
+                h_out[(size_t)t * d + r] = x[(size_t)t * d + r] * sc;
+        }
+    }
+}
+
+int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const float* logits_in,
+                          int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
+                          int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
+                          int32_t* perm, int32_t* inv_perm, float* xg, hipStream_t s) {
+    const int N = T * k;
+    const unsigned grid = (unsigned)(N < 32 ? N : 32);
+    if (norm)
+        hipLaunchKernelGGL(gate_small_kernel<true>, dim3(grid), dim3(PERM_THREADS), 0, s, x, w_gate,
+                           logits_in, T, d, E, k, eps, h_out, logits_out, idx, weights, counts,
+                           offsets, perm, inv_perm, xg);
+    else
+        hipLaunchKernelGGL(gate_small_kernel<false>, dim3(grid), dim3(PERM_THREADS), 0, s, x, w_gate,
+                           logits_in, T, d, E, k, eps, h_out, logits_out, idx, weights, counts,
+                           offsets, perm, inv_perm, xg);
+    return moe_launch_status();
+}
+
+// ------------------------------------------------ combine + residual add ----
+__global__ __launch_bounds__(256) void combine_residual_kernel(const float4* __restrict__ yg,
+                                                               const int32_t* __restrict__ inv_perm,
+                                                               const float* __restrict__ weights,
+                                                               int T, int k, int row_chunks,
+                                                               float4* __restrict__ x) {
+    const int t = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T || c >= row_chunks) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; j++) {
+        const float w = weights[(size_t)t * k + j];
+        const float4 v = yg[(size_t)inv_perm[(size_t)t * k + j] * row_chunks + c];
+        acc.x += w * v.x;
+        acc.y += w * v.y;
+        acc.z += w * v.z;
+        acc.w += w * v.w;
+    }
+    float4 r = x[(size_t)t * row_chunks + c];
+    r.x += acc.x; r.y += acc.y; r.z += acc.z; r.w += acc.w;
+    x[(size_t)t * row_chunks + c] = r;
+}
+
+int moe_combine_residual_launch(const float* yg, const int32_t* inv_perm, const float* weights, int T,
+                                int k, int d, float* x, hipStream_t s) {
+    const int row_chunks = d / 4;
+    dim3 grid((unsigned)((row_chunks + 255) / 256), 1);
+    for (int t0 = 0; t0 < T; t0 += 65535) {
+        const int tn = (T - t0) < 65535 ? (T - t0) : 65535;
+        grid.y = (unsigned)tn;
+        hipLaunchKernelGGL(combine_residual_kernel, grid, dim3(256), 0, s, (const float4*)yg,
+                           inv_perm + (size_t)t0 * k, weights + (size_t)t0 * k, tn, k, row_chunks,
+                           (float4*)(x + (size_t)t0 * d));
+    }
+    return moe_launch_status();
+}

@@ -42,7 +42,65 @@ def test_support_kernels(moe):
         assert (to_host(xd) == x + y).all()
 
 
-def _run_stack(moe, cfgs, T, k):
+def test_fused_front_ends_match_separate_calls(moe):
+    rng = np.random.default_rng(11)
+    d, E, k = 4096, 8, 2
+    wg = to_dev((rng.standard_normal((d, E)) / np.sqrt(d)).astype(np.float32))
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def outs(T, N):
+        return (torch.zeros(E, **i32), torch.zeros(E + 1, **i32), torch.zeros(N, **i32),
+                torch.zeros(N, **i32), torch.zeros((N, d), device="cuda"))
+
+    for T in (1, 2, 4, 7, 16):
+        N = T * k
+        x = to_dev(rng.standard_normal((T, d)).astype(np.float32) * 2.0)
+        # --- route + permute on given logits ---
+        lg = to_dev(rng.standard_normal((T, E)).astype(np.float32))
+        idx_s, w_s = moe.moe_route(lg, k)
+        sep = moe.moe_permute(idx_s, E, x)
+        idx_f = torch.zeros((T, k), **i32)
+        w_f = torch.zeros((T, k), device="cuda")
+        fo = outs(T, N)
+        moe.moe_route_permute(lg, k, x, idx_f, w_f, fo)
+        assert torch.equal(idx_f, idx_s) and torch.equal(w_f, w_s)
+        for a, b in zip(fo, sep):
+            assert torch.equal(a, b)
+        # oracle: bit-exact routing on the same logits
+        ref_idx, _ = orc.route(to_host(lg), k)
+        assert (to_host(idx_f) == ref_idx).all()
+        if T > 4:
+            continue
+        # --- rmsnorm + logits + route + permute ---
+        h_s = moe.moe_rmsnorm(x, 1e-5)
+        h_f = torch.zeros_like(x)
+        lg_f = torch.zeros((T, E), device="cuda")
+        fo = outs(T, N)
+        moe.moe_norm_route_permute(x, wg, k, 1e-5, h_f, lg_f, idx_f, w_f, fo)
+        assert max_rel(to_host(h_f), to_host(h_s)) <= 2e-6
+        lg_ref = orc.router_logits(to_host(h_f).astype(np.float64), to_host(wg))
+        assert np.max(np.abs(to_host(lg_f) - lg_ref)) <= 2e-5 * max(1.0, np.max(np.abs(lg_ref)))
+        # routing is bit-exact on the logits the kernel itself reports
+        ref_idx, ref_w = orc.route(to_host(lg_f), k)
+        assert (to_host(idx_f) == ref_idx).all()
+        assert np.max(np.abs(to_host(w_f) - ref_w)) <= 1e-6
+        rc, ro, rp, ri, _ = orc.permute(ref_idx, E, np.zeros((T, 1)))
+        assert (to_host(fo[0]) == rc).all() and (to_host(fo[1]) == ro).all()
+        assert (to_host(fo[2]) == rp).all() and (to_host(fo[3]) == ri).all()
+        assert torch.equal(fo[4], h_f[torch.from_numpy(rp // k).cuda().long()])
+    # combine + residual == combine then add
+    T = 5
+    yg = to_dev(rng.standard_normal((T * k, d)).astype(np.float32))
+    inv = to_dev(rng.permutation(T * k).astype(np.int32))
+    w = to_dev(rng.random((T, k)).astype(np.float32))
+    x0 = rng.standard_normal((T, d)).astype(np.float32)
+    xa, xb = to_dev(x0.copy()), to_dev(x0.copy())
+    moe.moe_combine_residual(yg, inv, w, xa)
+    moe.moe_residual_add(xb, moe.moe_combine(yg, inv, w))
+    assert torch.equal(xa, xb)
+
+
+def _run_stack(moe, cfgs, T, k, fused=True):
     """cfgs: one MoEConfig per layer.  Returns (gpu final x, oracle result, info)."""
     host_layers, dev_layers = [], []
     for cfg in cfgs:
@@ -54,7 +112,7 @@ def _run_stack(moe, cfgs, T, k):
     x0 = mi.normal_f32(cfgs[0].seed, 0, (T, cfgs[0].d))
     xd = to_dev(x0.copy())
     logits, idx = [], []
-    moe.moe_stack_forward(dev_layers, xd, k, logits_out=logits, idx_out=idx)
+    moe.moe_stack_forward(dev_layers, xd, k, logits_out=logits, idx_out=idx, fused=fused)
     torch.cuda.synchronize()
     gpu_logits = [to_host(t) for t in logits]
     ref = orc.stack(x0.astype(np.float64), host_layers, k, forced_logits=gpu_logits)
@@ -68,12 +126,13 @@ def _run_stack(moe, cfgs, T, k):
                                   err_free=max_rel(to_host(xd), free["x"]))
 
 
-@pytest.mark.parametrize("T,L,d,f", [(1, 6, 256, 512), (24, 4, 256, 512), (300, 3, 256, 512),
-                                     (7, 4, 512, 1024)])
-def test_stack_small_shapes(moe, T, L, d, f):
+@pytest.mark.parametrize("T,L,d,f,fused", [(1, 6, 256, 512, True), (1, 6, 256, 512, False),
+                                           (3, 4, 256, 512, True), (24, 4, 256, 512, True),
+                                           (300, 3, 256, 512, True), (7, 4, 512, 1024, False)])
+def test_stack_small_shapes(moe, T, L, d, f, fused):
     cfgs = [mi.small_config(f"s{l}", T, d, f, 8, 2, 3000 + 10 * l + T, w_dtype=mi.BF16)
             for l in range(L)]
-    x, ref, info = _run_stack(moe, cfgs, T, 2)
+    x, ref, info = _run_stack(moe, cfgs, T, 2, fused=fused)
     err = max_rel(x, ref["x"])
     print(f"stack T={T} L={L} d={d}: err={err:.3e} {info}")
     assert err <= TOL_BF16
