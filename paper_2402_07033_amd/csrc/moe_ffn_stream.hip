@@ -96,10 +96,13 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
              i += (size_t)gridDim.x * blockDim.x)
             z[i] = zero;
     }
+    __shared__ int s_offs[MOE_MAX_E + 1];
+    if (tid <= a.E) s_offs[tid] = a.offsets[tid];  // one parallel fetch, then a serial walk in LDS
+    __syncthreads();
     if (tid == 0) {
         int n = 0;
         for (int e = 0; e < a.E; e++) {
-            int lo = a.offsets[e], hi = a.offsets[e + 1];
+            int lo = s_offs[e], hi = s_offs[e + 1];
             lo = lo < 0 ? 0 : (lo > a.N ? a.N : lo);
             hi = hi < lo ? lo : (hi > a.N ? a.N : hi);
             for (int r = lo; r < hi && n < ST_MAX_TILES; r += 16) {
@@ -182,7 +185,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
             s_red[it & 1][wave][m][lane] = v;
         }
         __syncthreads();
-        if (wave == 0) {
+        if (wave == it % a.W) {  // the waves take turns at the epilogue
             f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
             for (int w = 0; w < a.W; w++) {
                 sa += s_red[it & 1][w][0][lane];
