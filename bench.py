@@ -33,6 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # from those profile runs, not measured by this script.
 TRAFFIC_BYTES = {
     "decode_t1": 470.5e6,       # profiles/stream_kernels_decode_t1.txt
+    "beam_t16": 1.604e9,        # profiles/stream_kernels_beam_t16.txt (6.8 active experts)
     "prefill_t4096": 4.82e9,    # profiles/grouped_gemm_prefill_t4096.txt (fetch 4.58 GB + write 0.24 GB)
 }
 
