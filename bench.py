@@ -127,6 +127,7 @@ class Step:
     def __init__(self, torch, moe, T, x_dtype, fused_gate=False):
         N = T * K
         self.fused_gate = fused_gate and T <= 16 and x_dtype == torch.float32
+        self.ffn_path = moe.MOE_FFN_AUTO
         i32 = dict(dtype=torch.int32, device="cuda")
         f32 = dict(dtype=torch.float32, device="cuda")
         self.moe = moe
@@ -151,7 +152,7 @@ class Step:
                                                                   out=self.perm_out)
         if ev is not None:
             events.record(ev[0], stream)
-        moe.moe_expert_ffn(W, xg, offsets, workspace=self.ws, yg=self.yg)
+        moe.moe_expert_ffn(W, xg, offsets, workspace=self.ws, yg=self.yg, path=self.ffn_path)
         if ev is not None:
             events.record(ev[2], stream)
         moe.moe_combine(self.yg, inv_perm, self.w, self.y)
@@ -185,7 +186,7 @@ def cpu_baseline(torch, wl, host_w, xs, lgs, budget_s=15.0):
         t_used += time.perf_counter() - t0
         done_tokens += per_call
         i += 1
-        if time.perf_counter() - t_start > budget_s or done_tokens >= 256:
+        if time.perf_counter() - t_start > budget_s or done_tokens >= 512:
             break
     return dict(value=done_tokens / t_used, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
                 sample=f"{done_tokens} tokens of this workload, {per_call} per oracle call, "
@@ -255,7 +256,7 @@ def run_stack(args, torch, moe, wl):
         "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights x fp32 activations" + (" (bf16 hi+lo)" if T * K <= 32 else
+        "dtype": "bf16 weights x fp32 activations" + (" (bf16 hi+lo)" if T * K <= 96 else
                                                       " (rounded to bf16)") + ", fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "layers": L, "d_model": D, "d_ff": F,
@@ -317,6 +318,10 @@ def main():
     ap.add_argument("--workload", default="decode_t1", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="override T of a single-layer workload (sweeps; the JSON names it)")
+    ap.add_argument("--ffn-path", default="auto", choices=["auto", "stream", "grouped"],
+                    help="force the expert-FFN kernel family (sweeps)")
     ap.add_argument("--fused-gate", action="store_true",
                     help="decode-sized workloads: use the one-launch moe_route_permute instead "
                          "of moe_route + moe_permute (same outputs)")
@@ -340,7 +345,9 @@ def main():
         print(json.dumps({"mfma_sustained_TFLOPs_bf16_16x16x32": mfma_ceiling(torch, moe),
                           "published_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS}))
         return
-    wl = WORKLOADS[args.workload]
+    wl = dict(WORKLOADS[args.workload])
+    if args.tokens is not None and "layers" not in wl:
+        wl["T"] = args.tokens
     T = wl["T"]
     if "layers" in wl:
         return run_stack(args, torch, moe, wl)
@@ -360,6 +367,8 @@ def main():
     torch.cuda.empty_cache()
     xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
     step = Step(torch, moe, T, xs[0].dtype, fused_gate=args.fused_gate)
+    step.ffn_path = {"auto": moe.MOE_FFN_AUTO, "stream": moe.MOE_FFN_STREAM,
+                     "grouped": moe.MOE_FFN_GROUPED}[args.ffn_path]
     stream = torch.cuda.current_stream().cuda_stream
     events = HipEvents()
 
@@ -437,7 +446,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "d_model": D, "d_ff": F, "experts": E,
                    "top_k": K, "weight_sets_rotated": n_layers, "inputs_rotated": n_inputs,
-                   "counts_first_input": counts_all[0],
+                   "counts_first_input": counts_all[0], "ffn_path": args.ffn_path,
                    "calls_per_step": ("moe_route_permute, moe_expert_ffn, moe_combine"
                                       if step.fused_gate else
                                       "moe_route, moe_permute, moe_expert_ffn, moe_combine")},

@@ -44,7 +44,7 @@ typedef enum {
     MOE_ERR_HIP = -4          /* a HIP runtime call failed (allocation, launch) */
 } moe_status_t;
 
-/* Which expert-FFN kernels to run.  AUTO picks from N and the shape. */
+/* Which expert-FFN kernels to run.  AUTO picks from N and the shape (STREAM up to 96 rows). */
 typedef enum {
     MOE_FFN_AUTO = 0,
     MOE_FFN_STREAM = 1, /* decode: weight-streaming MFMA kernels, <=16 rows per pass */

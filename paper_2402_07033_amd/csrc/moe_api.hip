@@ -103,9 +103,10 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
         return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
     }
     if (path == MOE_FFN_AUTO) {
-        // Up to 32 routed rows (16 tokens, top-2) no expert has more than one
-        // 16-row tile and the layer is weight-bandwidth bound: stream.
-        path = (N <= 32 && moe_ffn_stream_supported(W->d, W->f)) ? MOE_FFN_STREAM
+        // Few routed rows: the layer is weight-bandwidth bound and the streaming kernels
+        // read each active expert once per 16-row tile at ~6 TB/s.  Measured crossover with
+        // the grouped kernels (Mixtral shape, Zipf-skewed routing): between 96 and 128 rows.
+        path = (N <= 96 && moe_ffn_stream_supported(W->d, W->f)) ? MOE_FFN_STREAM
                                                                    : MOE_FFN_GROUPED;
     }
     if (path == MOE_FFN_STREAM)
