@@ -180,3 +180,61 @@ def test_ffn_rejects_short_workspace_and_bad_path(moe):
         moe.moe_expert_ffn(W, xg, off, path=7)
     assert ei.value.status == -1
     W.free()
+
+
+# ------------------------------------------------------------ edge cases ----
+
+def test_empty_inputs_are_noops(moe):
+    z = torch.empty((0, 8), device="cuda")
+    idx, w = moe.moe_route(z, 2)
+    assert tuple(idx.shape) == (0, 2) and tuple(w.shape) == (0, 2)
+    cfg = mi.small_config("e", 4, 256, 512, 8, 2, 5, w_dtype=mi.BF16)
+    li = mi.make_layer(cfg, threads=1)
+    W = pack_layer(li)
+    off = torch.zeros(9, dtype=torch.int32, device="cuda")
+    yg = moe.moe_expert_ffn(W, torch.empty((0, 256), device="cuda"), off)
+    assert tuple(yg.shape) == (0, 256)
+    y = moe.moe_combine(yg, torch.empty(0, dtype=torch.int32, device="cuda"),
+                        torch.empty((0, 2), device="cuda"))
+    assert tuple(y.shape) == (0, 256)
+    W.free()
+
+
+@pytest.mark.parametrize("path_name,T,xdt", [("stream", 16, mi.F32), ("stream", 48, mi.F32),
+                                             ("grouped", 16, mi.BF16), ("grouped", 700, mi.BF16)])
+def test_all_tokens_to_one_expert_and_k_equals_E(moe, path_name, T, xdt):
+    path = moe.MOE_FFN_STREAM if path_name == "stream" else moe.MOE_FFN_GROUPED
+    # every token picks experts (5, 2) in that order: six experts stay empty
+    cfg = mi.small_config("one", T, 256, 512, 8, 2, 900 + T, w_dtype=mi.BF16, x_dtype=xdt)
+    li = mi.make_layer(cfg, threads=1)
+    lg = np.full((T, 8), -4.0, np.float32)
+    lg[:, 5] = 3.0
+    lg[:, 2] = 1.0
+    li.logits = lg
+    _layer_parity(moe, cfg, li, TOL_BF16, path=path)
+    # k == E: every expert used by every token (full softmax)
+    cfg = mi.small_config("kE", T, 256, 512, 4, 4, 950 + T, w_dtype=mi.BF16, x_dtype=xdt,
+                          zipf_s=1.2)
+    _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16, path=path)
+
+
+def test_single_expert_layer_and_auto_threshold(moe):
+    cfg = mi.small_config("E1", 9, 256, 512, 1, 1, 77, w_dtype=mi.BF16)
+    _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16)
+    # AUTO on either side of the stream/grouped switch (96 routed rows)
+    for T in (48, 49):
+        cfg = mi.small_config("thr", T, 256, 512, 8, 2, 80 + T, w_dtype=mi.BF16, zipf_s=1.2)
+        _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16)
+
+
+def test_grouped_path_is_deterministic(moe):
+    cfg = mi.small_config("det", 300, 256, 512, 8, 2, 31, w_dtype=mi.BF16, x_dtype=mi.BF16,
+                          zipf_s=1.2)
+    li = mi.make_layer(cfg, threads=1)
+    W = pack_layer(li)
+    x, lg = to_dev(li.x), to_dev(li.logits)
+    first = moe.moe_layer(W, x, lg, 2, path=moe.MOE_FFN_GROUPED)["yg"].clone()
+    for _ in range(5):
+        again = moe.moe_layer(W, x, lg, 2, path=moe.MOE_FFN_GROUPED)["yg"]
+        assert torch.equal(first, again)
+    W.free()
