@@ -123,6 +123,8 @@ struct GroupedArgs {
     int NT;      // workgroup tiles along the features = FR / GG_FROWS
     int KS_out;  // up: f/32 (fragment columns of hp); down: unused
     int C;       // down: d (row length of yg)
+    int split;   // down: deal the left-over tiles of each XCD in pieces of their reduction
+    float* part; // down, split: partial tiles [8 XCDs][workgroups per XCD][2][256][256] fp32
 };
 
 // s_waitcnt with only one counter constrained (gfx9 encoding: vmcnt = bits 3:0 and
@@ -136,6 +138,10 @@ struct TileInfo {
     int nt;    // feature tile
     int blk0;  // first block of the tile inside the segment
     int nblk;  // blocks of the tile that exist (1..16)
+    // the part of the tile's reduction this unit of work covers (whole tile: 0, KS)
+    int k_lo, klen;
+    bool partial;
+    int piece;  // 0 or 1: which of this workgroup's two partial-tile slots it writes
 };
 
 // Number of logical tiles = NT * sum_e ceil(M_e / 256).
@@ -169,6 +175,10 @@ __device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offse
             ti.si.e = e; ti.si.row0 = lo; ti.si.rows = hi - lo; ti.si.bbase = bb;
             ti.blk0 = ti.tis * GG_TILE_BLOCKS;
             ti.nblk = (nb - ti.blk0) < GG_TILE_BLOCKS ? (nb - ti.blk0) : GG_TILE_BLOCKS;
+            ti.k_lo = 0;
+            ti.klen = 0;  // filled in by the caller
+            ti.partial = false;
+            ti.piece = 0;
             return true;
         }
         base += tiles * NT;
@@ -195,12 +205,12 @@ __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo
 #pragma unroll
     for (int j = 0; j < 4; j++)
         ts.a[j] = a.wfrag +
-                  (((size_t)ti.si.e * a.FR + (size_t)ti.nt * GG_FROWS + 4 * wave + j) * a.KS) * 64;
+                  (((size_t)ti.si.e * a.FR + (size_t)ti.nt * GG_FROWS + 4 * wave + j) * a.KS + ti.k_lo) * 64;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         int blk = 4 * wave + i;
         blk = blk < ti.nblk ? blk : ti.nblk - 1;  // clamp: every wave always issues 4 requests
-        ts.b[i] = a.bfrag + (((size_t)(ti.si.bbase + ti.blk0 + blk)) * a.KS) * 64;
+        ts.b[i] = a.bfrag + (((size_t)(ti.si.bbase + ti.blk0 + blk)) * a.KS + ti.k_lo) * 64;
     }
 }
 
@@ -212,26 +222,77 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // fragment rows [4*wave, +4)
     const unsigned voff = (unsigned)lane * 16u;                  // byte offset inside a fragment
-    const int KT = a.KS;                                         // multiple of 4, >= GG_NS
 
-    // this workgroup's tiles: logical indices xcd*per_xcd + slot, slot = id/8, id/8 + wgs, ...
+    // This workgroup's units of work.  The logical tiles of XCD x are x*per_xcd ... ; the
+    // 32 workgroups of an XCD take them round-robin (slot = id/8, id/8 + wgs, ...).  When
+    // the tile count is not a multiple of the workgroup count the last round would leave
+    // most CUs idle (560 second-projection tiles over 256 CUs = 2.19 rounds), so for the
+    // second projection (linear in the reduction) the left-over tiles are cut along the
+    // reduction instead, in equal pieces for all workgroups; every piece stores its partial
+    // tile into scratch and gg_fixup_kernel adds the pieces of a tile in a fixed order.
     const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
     const int per_xcd = (total + 7) / 8;
     const int xcd = blockIdx.x & 7;
-    const int wgs_per_xcd = gridDim.x >> 3;
-    int slot = blockIdx.x >> 3;
-    auto tile_at = [&](int sl, TileInfo& ti) -> bool {
-        if (sl >= per_xcd) return false;
-        const int L = xcd * per_xcd + sl;
-        return L < total && gg_decode_tile(a.offsets, a.E, a.N, a.NT, L, ti);
+    const int wgs = gridDim.x >> 3;
+    const int me = blockIdx.x >> 3;
+    int chunk = total - xcd * per_xcd;
+    chunk = chunk < 0 ? 0 : (chunk > per_xcd ? per_xcd : chunk);  // tiles of this XCD
+    const bool split = !UP && a.split && (chunk % wgs) != 0;
+    const int n_full = split ? chunk / wgs : (chunk - me + wgs - 1) / wgs;  // whole tiles I own
+    // pieces of the left-over tiles (slots n_full*wgs ... chunk-1) for this workgroup
+    int pc_tile[2] = {0, 0}, pc_lo[2] = {0, 0}, pc_len[2] = {0, 0}, n_pieces = 0;
+    if (split) {
+        const int R = chunk - n_full * wgs;
+        const int S = R * a.KS;
+        int per = (((S + wgs - 1) / wgs) + 3) & ~3;
+        per = per < 32 ? 32 : per;
+        // cut points are snapped so that no piece is shorter than 8 steps
+        auto snap = [&](int c) -> int {
+            if (c >= S) return S;
+            const int r = c % a.KS;
+            if (r < 8) return c - r;
+            if (a.KS - r < 8) return c + (a.KS - r);
+            return c;
+        };
+        const int c0 = snap(me * per), c1 = snap((me + 1) * per);
+        if (c0 < c1) {
+            const int rA = c0 / a.KS;
+            const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
+            pc_tile[0] = rA; pc_lo[0] = c0 - rA * a.KS; pc_len[0] = endA - c0;
+            n_pieces = 1;
+            if (c1 > endA) {
+                pc_tile[1] = rA + 1; pc_lo[1] = 0; pc_len[1] = c1 - endA;
+                n_pieces = 2;
+            }
+        }
+    }
+    const int n_units = n_full + n_pieces;
+    auto unit_at = [&](int n, TileInfo& ti) -> bool {
+        if (n >= n_units) return false;
+        int sl, lo = 0, len = a.KS;
+        if (n < n_full) {
+            sl = me + n * wgs;
+        } else {
+            sl = n_full * wgs + pc_tile[n - n_full];
+            lo = pc_lo[n - n_full];
+            len = pc_len[n - n_full];
+        }
+        if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + sl, ti)) return false;
+        ti.k_lo = lo;
+        ti.klen = len;
+        ti.partial = (len != a.KS);
+        ti.piece = n < n_full ? 0 : n - n_full;
+        return true;
     };
 
+    int unit = 0;
     TileInfo cur, nxt;
-    if (!tile_at(slot, cur)) return;
-    bool has_next = tile_at(slot + wgs_per_xcd, nxt);
+    if (!unit_at(unit, cur)) return;
+    bool has_next = unit_at(unit + 1, nxt);
     TileSrc scur, snxt;
     gg_tile_src(a, cur, wave, scur);
     if (has_next) gg_tile_src(a, nxt, wave, snxt); else snxt = scur;
+    int KT = cur.klen;  // steps of the current unit: a multiple of 4, >= GG_NS
 
     // look-ahead sources: reduction step j of the current tile, or j-KT of the next one
     auto b_src = [&](int i, int j) -> const char* {
@@ -374,26 +435,86 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
                     *(uint2*)dst = pk;
                 }
             } else {
+                // whole tiles go to yg; pieces of a tile to this workgroup's scratch slot
+                // (same code, only the destination differs)
                 const int r_in_seg = blk * 16 + t;
                 if (r_in_seg < cur.si.rows) {
-                    float* row = (float*)a.out + (size_t)(cur.si.row0 + r_in_seg) * a.C;
+                    float* row =
+                        cur.partial
+                            ? a.part + ((((size_t)xcd * wgs + me) * 2 + cur.piece) * 256 + i * 16 + t) * 256 +
+                                  (4 * wave) * 16 + 4 * fq
+                            : (float*)a.out + (size_t)(cur.si.row0 + r_in_seg) * a.C +
+                                  (cur.nt * GG_FROWS + 4 * wave) * 16 + 4 * fq;
 #pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        const int feat = (cur.nt * GG_FROWS + 4 * wave + j) * 16 + 4 * fq;
-                        *(float4*)(row + feat) =
+                    for (int j = 0; j < 4; j++)
+                        *(float4*)(row + j * 16) =
                             make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-                    }
                 }
             }
         }
         if (!has_next) break;
-        // advance: next becomes current; look one tile further ahead
-        slot += wgs_per_xcd;
+        // advance: next becomes current; look one unit further ahead
+        unit++;
         cur = nxt;
         scur = snxt;
-        has_next = tile_at(slot + wgs_per_xcd, nxt);
+        KT = cur.klen;
+        has_next = unit_at(unit + 1, nxt);
         if (has_next) gg_tile_src(a, nxt, wave, snxt);
         GG_WAIT_LGKM(0);  // scalar loads of the decode must not sit in the LDS read counter
+    }
+}
+
+// Adds the pieces of every left-over tile of the second projection into yg, in the order
+// of the workgroups that produced them (deterministic).  One workgroup per (XCD, left-over
+// tile); it recomputes the same cut points the GEMM workgroups used.
+__global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs) {
+    __shared__ int s_slot[80];
+    __shared__ int s_n;
+    const int xcd = blockIdx.x / wgs, r = blockIdx.x % wgs;
+    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
+    const int per_xcd = (total + 7) / 8;
+    int chunk = total - xcd * per_xcd;
+    chunk = chunk < 0 ? 0 : (chunk > per_xcd ? per_xcd : chunk);
+    if (chunk % wgs == 0) return;
+    const int n_full = chunk / wgs;
+    const int R = chunk - n_full * wgs;
+    if (r >= R) return;
+    TileInfo ti;
+    if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + n_full * wgs + r, ti)) return;
+    if (threadIdx.x == 0) {
+        const int S = R * a.KS;
+        int per = (((S + wgs - 1) / wgs) + 3) & ~3;
+        per = per < 32 ? 32 : per;
+        auto snap = [&](int c) -> int {
+            if (c >= S) return S;
+            const int q = c % a.KS;
+            if (q < 8) return c - q;
+            if (a.KS - q < 8) return c + (a.KS - q);
+            return c;
+        };
+        int n = 0;
+        for (int j = 0; j < wgs; j++) {
+            const int c0 = snap(j * per), c1 = snap((j + 1) * per);
+            if (c0 >= c1) continue;
+            const int rA = c0 / a.KS;
+            const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
+            if (rA == r && n < 80) s_slot[n++] = (xcd * wgs + j) * 2 + 0;
+            if (c1 > endA && rA + 1 == r && n < 80) s_slot[n++] = (xcd * wgs + j) * 2 + 1;
+        }
+        s_n = n;
+    }
+    __syncthreads();
+    const int n = s_n;
+    const int rows = (ti.si.rows - ti.blk0 * 16) < 256 ? (ti.si.rows - ti.blk0 * 16) : 256;
+    for (int idx = threadIdx.x; idx < rows * 64; idx += 256) {
+        const int row = idx >> 6, c4 = idx & 63;
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int p = 0; p < n; p++) {
+            const float4 v = *(const float4*)(a.part + ((size_t)s_slot[p] * 256 + row) * 256 + c4 * 4);
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        *(float4*)((float*)a.out + (size_t)(ti.si.row0 + ti.blk0 * 16 + row) * a.C +
+                   ti.nt * GG_FROWS * 16 + c4 * 4) = sum;
     }
 }
 
@@ -401,9 +522,15 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
 static inline size_t gg_align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline size_t gg_max_blocks(int N, int E) { return (size_t)N / 16 + E; }
 
+// scratch for the partial tiles of the second projection: 2 slots of 256 x 256 fp32 per
+// persistent workgroup (one workgroup per CU, rounded up to a multiple of 8)
+static inline size_t gg_part_bytes() {
+    return (size_t)((moe_num_cus() + 7) / 8 * 8) * 2 * 256 * 256 * sizeof(float);
+}
+
 size_t moe_ffn_grouped_workspace(int N, int E, int d, int f) {
     const size_t nb = gg_max_blocks(N, E);
-    return gg_align256(nb * 16 * d * 2) + gg_align256(nb * 16 * f * 2);
+    return gg_align256(nb * 16 * d * 2) + gg_align256(nb * 16 * f * 2) + gg_part_bytes();
 }
 
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
@@ -449,6 +576,8 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.NT = up.FR / GG_FROWS;
     up.KS_out = f / 32;
     up.C = 0;
+    up.split = 0;
+    up.part = nullptr;
     hipLaunchKernelGGL(gg_gemm_kernel<true>, dim3(pgrid), dim3(GG_THREADS), lds_bytes, s, up);
     moe_record_mid_event(s);
 
@@ -463,6 +592,13 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.NT = dn.FR / GG_FROWS;
     dn.KS_out = 0;
     dn.C = d;
+    // Cutting left-over tiles along the reduction needs pieces of >= 32 steps; the pieces
+    // are stored in scratch behind hp and summed by gg_fixup_kernel.
+    dn.split = (f / 32 >= 64) ? 1 : 0;
+    dn.part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
+                       gg_align256(nb * 16 * f * 2));
     hipLaunchKernelGGL(gg_gemm_kernel<false>, dim3(pgrid), dim3(GG_THREADS), lds_bytes, s, dn);
+    if (dn.split)
+        hipLaunchKernelGGL(gg_fixup_kernel, dim3(pgrid), dim3(256), 0, s, dn, (int)(pgrid / 8));
     return moe_launch_status();
 }
