@@ -44,10 +44,15 @@ WORKLOADS = {
     "prefill_t4096": dict(T=4096, x_bf16=True, zipf=1.2, bound="mfma"),
     # 32-layer stack of MoE blocks (RMSNorm -> router -> experts -> residual), all ~90 GB of
     # expert matrices resident; a step is one pass through all layers
+    # second layer shape (paper, App. E: a 16-expert top-2 model): d=4096, f=6400, E=16
+    "e16_decode_t1": dict(T=1, x_bf16=False, zipf=None, bound="hbm", shape=(4096, 6400, 16, 2)),
+    "e16_beam_t16": dict(T=16, x_bf16=False, zipf=1.2, bound="hbm", shape=(4096, 6400, 16, 2)),
+    "e16_prefill_t4096": dict(T=4096, x_bf16=True, zipf=1.2, bound="mfma",
+                              shape=(4096, 6400, 16, 2)),
     "stack_t1": dict(T=1, x_bf16=False, zipf=None, bound="hbm", layers=32),
     "stack_t512": dict(T=512, x_bf16=False, zipf=None, bound="hbm", layers=32),
 }
-D, F, E, K = 4096, 14336, 8, 2
+D, F, E, K = 4096, 14336, 8, 2  # Mixtral-8x7B layer; main() replaces it by wl["shape"]
 
 
 class HipEvents:
@@ -346,6 +351,8 @@ def main():
                           "published_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS}))
         return
     wl = dict(WORKLOADS[args.workload])
+    global D, F, E, K
+    D, F, E, K = wl.get("shape", (D, F, E, K))
     if args.tokens is not None and "layers" not in wl:
         wl["T"] = args.tokens
     T = wl["T"]

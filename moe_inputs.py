@@ -67,6 +67,13 @@ CONFIGS = {
     "beam_t16": MoEConfig("beam_t16", 16, 4096, 14336, 8, 2, BF16, F32, 1003, 1.2, 1002),
     "prefill_t4096": MoEConfig("prefill_t4096", 4096, 4096, 14336, 8, 2, BF16, BF16, 1004, 1.2,
                                1002),
+    # second layer shape (paper, App. E evaluates a 16-expert top-2 model): d=4096, f=6400,
+    # E=16; the layer arithmetic is the same, only the shape differs.  One weight set
+    # (seed 1005) serves the three workloads.
+    "e16_decode_t1": MoEConfig("e16_decode_t1", 1, 4096, 6400, 16, 2, BF16, F32, 1005),
+    "e16_beam_t16": MoEConfig("e16_beam_t16", 16, 4096, 6400, 16, 2, BF16, F32, 1006, 1.2, 1005),
+    "e16_prefill_t4096": MoEConfig("e16_prefill_t4096", 4096, 4096, 6400, 16, 2, BF16, BF16, 1007,
+                                   1.2, 1005),
 }
 
 

@@ -1,5 +1,6 @@
-"""GPU parity at the full Mixtral-8x7B layer shape (d=4096, f=14336, E=8,
-top-2, bf16 weights), in the launch configuration bench.py times.
+"""GPU parity at the full layer shapes bench.py times: Mixtral-8x7B (d=4096,
+f=14336, E=8, top-2, bf16 weights) and the 16-expert shape (d=4096, f=6400,
+E=16, top-2), in the launch configuration of the bench.
 
 The oracle runs whole for the decode-sized workloads (1 and 16 tokens); for the
 4096-token prefill it runs on sampled rows of every expert segment (first, last
@@ -25,15 +26,32 @@ def moe():
     return m
 
 
+def _weights(cfg_name):
+    cfg = mi.CONFIGS[cfg_name]
+    w1, w3, w2 = mi.make_weights(cfg, threads=16)
+    W = pack_layer(mi.LayerInputs(cfg, None, None, w1, w3, w2))
+    return dict(w1=w1, w3=w3, w2=w2, W=W)
+
+
 @pytest.fixture(scope="module")
 def mixtral(moe):
     """One set of Mixtral-shaped expert matrices (weight seed 1002), host + packed."""
-    cfg = mi.CONFIGS["decode_t1"]
-    w1, w3, w2 = mi.make_weights(cfg, threads=16)
-    li = mi.LayerInputs(cfg, None, None, w1, w3, w2)
-    W = pack_layer(li)
-    yield dict(w1=w1, w3=w3, w2=w2, W=W)
-    W.free()
+    m = _weights("decode_t1")
+    yield m
+    m["W"].free()
+
+
+@pytest.fixture(scope="module")
+def e16(moe):
+    """One set of 16-expert-shaped matrices (weight seed 1005), host + packed."""
+    m = _weights("e16_decode_t1")
+    yield m
+    m["W"].free()
+
+
+@pytest.fixture
+def shape_weights(request):
+    return request.getfixturevalue("e16" if request.param.startswith("e16") else "mixtral")
 
 
 def _check_index_outputs(out, ref):
@@ -42,8 +60,13 @@ def _check_index_outputs(out, ref):
     assert np.max(np.abs(to_host(out["w"]) - ref["w"])) <= TOL_GATE
 
 
-@pytest.mark.parametrize("name", ["decode_t1", "beam_t16"])
-def test_decode_sized_layer_full(moe, mixtral, name):
+DECODE_SIZED = ["decode_t1", "beam_t16", "e16_decode_t1", "e16_beam_t16"]
+
+
+@pytest.mark.parametrize("name,shape_weights", [(n, n) for n in DECODE_SIZED],
+                         indirect=["shape_weights"])
+def test_decode_sized_layer_full(moe, shape_weights, name):
+    mixtral = shape_weights
     cfg = mi.CONFIGS[name]
     x, logits, _ = mi.make_activations(cfg)
     ref = orc.layer(mi.to_f64(x), logits, mixtral["w1"], mixtral["w3"], mixtral["w2"], cfg.k)
@@ -58,8 +81,12 @@ def test_decode_sized_layer_full(moe, mixtral, name):
     assert max_rel(to_host(out2["y"]), ref["y"]) <= TOL_BF16
 
 
-def test_prefill_layer_sampled_rows(moe, mixtral):
-    cfg = mi.CONFIGS["prefill_t4096"]
+@pytest.mark.parametrize("name,shape_weights",
+                         [(n, n) for n in ["prefill_t4096", "e16_prefill_t4096"]],
+                         indirect=["shape_weights"])
+def test_prefill_layer_sampled_rows(moe, shape_weights, name):
+    mixtral = shape_weights
+    cfg = mi.CONFIGS[name]
     x, logits, _ = mi.make_activations(cfg)
     idx, w = orc.route(logits, cfg.k)
     counts, offsets, perm, inv_perm, _ = orc.permute(idx, cfg.E, np.zeros((cfg.T, 1)))
