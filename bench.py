@@ -238,8 +238,10 @@ def run_stack(args, torch, moe, wl):
     t0 = time.perf_counter()
     for _ in range(steps):
         one_pass()
+    t_enq = time.perf_counter()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    host_enqueue_ms = (t_enq - t0) * 1e3 / steps  # host time to issue one pass (no sync)
 
     # one more pass with events around each layer's first projection
     ev = [(events.create(), events.create()) for _ in range(L)]
@@ -267,6 +269,7 @@ def run_stack(args, torch, moe, wl):
         "config": {"workload": args.workload, "T": T, "layers": L, "d_model": D, "d_ff": F,
                    "experts": E, "top_k": K,
                    "per_token_expert_time_us": ms_per_step * 1e3 / T,
+                   "host_enqueue_ms": host_enqueue_ms,
                    "resident_expert_bytes": sum(W.nbytes for W, _ in layers)},
         "roofline": roofline,
     }

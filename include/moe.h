@@ -169,6 +169,17 @@ int moe_residual_add(float* x, const float* y, int T, int d, void* stream);
  *                           [T,E] are outputs; logits = (x . w_gate) / rms(x) in fp32.
  *   moe_combine_residual:   x[t,:] += sum_j weights[t,j] * yg[inv_perm[t*k+j], :]
  *                           (moe_combine + moe_residual_add), any T.
+ *   moe_combine_norm_route_permute: the seam between two blocks of a stack in one
+ *                           launch: moe_combine_residual of the block that just ran,
+ *                             x_out[t,:] = x_in[t,:] + sum_j weights_prev[t,j] *
+ *                                          yg_prev[inv_perm_prev[t*k_prev+j], :],
+ *                           then moe_norm_route_permute of x_out for the next block.
+ *                           Same limits (T <= 4, E <= 16) and the same fp32 arithmetic as
+ *                           the two separate calls.  Every workgroup reads the inputs while
+ *                           one writes the outputs, so x_out must not be x_in, and
+ *                           inv_perm / weights / xg must not be inv_perm_prev /
+ *                           weights_prev / yg_prev (MOE_ERR_INVALID_ARG otherwise); the
+ *                           caller keeps two sets of routing buffers and alternates.
  */
 int moe_route_permute(const float* logits, int T, int E, int k, const float* x, int d,
                       int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
@@ -179,6 +190,12 @@ int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, in
                            int32_t* inv_perm, float* xg, void* stream);
 int moe_combine_residual(const float* yg, const int32_t* inv_perm, const float* weights, int T,
                          int k, int d, float* x, void* stream);
+int moe_combine_norm_route_permute(const float* yg_prev, const int32_t* inv_perm_prev,
+                                   const float* weights_prev, int k_prev, const float* x_in,
+                                   float* x_out, const float* w_gate, int T, int d, int E, int k,
+                                   float eps, float* h, float* logits, int32_t* idx, float* weights,
+                                   int32_t* counts, int32_t* offsets, int32_t* perm,
+                                   int32_t* inv_perm, float* xg, void* stream);
 
 /*
  * Measurement hook: when `hip_event` (a hipEvent_t as void*, HOST handle) is

@@ -21,7 +21,7 @@ EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
            "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
            "moe_mfma_rate_probe", "moe_route_permute", "moe_norm_route_permute",
-           "moe_combine_residual")
+           "moe_combine_residual", "moe_combine_norm_route_permute")
 
 
 class MoeError(RuntimeError):
@@ -70,6 +70,9 @@ def lib():
         L.moe_norm_route_permute.restype = C.c_int
         L.moe_combine_residual.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
         L.moe_combine_residual.restype = C.c_int
+        L.moe_combine_norm_route_permute.argtypes = ([vp, vp, vp, i32, vp, vp, vp] + [i32] * 4 +
+                                                     [f32] + [vp] * 10)
+        L.moe_combine_norm_route_permute.restype = C.c_int
         for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
                   "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
                   "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
@@ -316,8 +319,27 @@ def moe_combine_residual(yg: torch.Tensor, inv_perm: torch.Tensor, weights: torc
     return x
 
 
+def moe_combine_norm_route_permute(yg_prev, inv_perm_prev, weights_prev, x_in, x_out, w_gate,
+                                   k: int, eps: float, h, logits, idx, weights, out, stream=None):
+    """Seam between two blocks in one launch: x_out = x_in + combine(yg_prev), then the
+    fused front end of the next block on x_out (T <= 4).  Outputs must not alias the
+    *_prev inputs."""
+    T, d = x_in.shape
+    E = w_gate.shape[1]
+    counts, offsets, perm, inv_perm, xg = out
+    _check(lib().moe_combine_norm_route_permute(
+        _ptr(yg_prev), _ptr(inv_perm_prev), _ptr(weights_prev), weights_prev.shape[1], _ptr(x_in),
+        _ptr(x_out), _ptr(w_gate), T, d, E, k, eps, _ptr(h), _ptr(logits), _ptr(idx),
+        _ptr(weights), _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(xg),
+        _stream(stream)), "moe_combine_norm_route_permute")
+    return out
+
+
 class StackBuffers:
-    """Preallocated device buffers for moe_stack_forward (one layer's worth, reused)."""
+    """Preallocated device buffers for moe_stack_forward (one layer's worth, reused).  The
+    routing outputs exist twice (sets 0 and 1, used by even and odd layers) because the
+    one-launch seam between two blocks reads the previous block's while writing the next
+    block's; x_alt is the second residual-stream buffer of that seam."""
 
     def __init__(self, T: int, E: int, k: int, d: int, f: int, device="cuda"):
         N = T * k
@@ -325,10 +347,13 @@ class StackBuffers:
         f32 = dict(dtype=torch.float32, device=device)
         self.h = torch.empty((T, d), **f32)
         self.logits = torch.empty((T, E), **f32)
-        self.idx = torch.empty((T, k), **i32)
-        self.w = torch.empty((T, k), **f32)
-        self.perm_out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
-                         torch.empty(N, **i32), torch.empty((N, d), **f32))
+        self.xg = torch.empty((N, d), **f32)
+        self.sets = [dict(idx=torch.empty((T, k), **i32), w=torch.empty((T, k), **f32),
+                          perm_out=(torch.empty(E, **i32), torch.empty(E + 1, **i32),
+                                    torch.empty(N, **i32), torch.empty(N, **i32), self.xg))
+                     for _ in range(2)]
+        self.idx, self.w, self.perm_out = (self.sets[0][n] for n in ("idx", "w", "perm_out"))
+        self.x_alt = torch.empty((T, d), **f32)
         self.ws = torch.empty(max(moe_expert_ffn_workspace(N, E, d, f, MOE_F32), 256),
                               dtype=torch.uint8, device=device)
         self.yg = torch.empty((N, d), **f32)
@@ -337,41 +362,57 @@ class StackBuffers:
 
 def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=None,
                       logits_out=None, idx_out=None, on_layer=None, fused: bool = True,
-                      stream=None):
+                      stream=None, seam: bool = True):
     """The layer-stack workload: for every (PackedWeights, w_gate) in `layers`
         h = rmsnorm(x); logits = h . w_gate; y = moe_layer(h, logits); x += y
     x (fp32 [T,d]) is updated in place.  logits_out / idx_out, when given, are lists
     that receive a copy of every layer's router logits / expert indices.  on_layer(l)
     is called before each layer's expert FFN is enqueued (measurement hook).  fused=True
-    uses the one-launch front end (T <= 4) and combine+residual; fused=False the separate
-    calls."""
+    uses the one-launch front end (T <= 4) and combine+residual, and with seam=True also
+    folds each block's combine+residual into the next block's front end; fused=False the
+    separate calls."""
     _dev(x, torch.float32, "x")
     T, d = x.shape
     W0 = layers[0][0]
     if bufs is None:
         bufs = StackBuffers(T, W0.E, k, d, W0.f, x.device)
     fused_gate = fused and T <= 4 and W0.E <= 16
+    seam = seam and fused_gate
+    cur = x  # residual stream: alternates between x and bufs.x_alt across seams
     for li, (W, w_gate) in enumerate(layers):
-        if fused_gate:
-            moe_norm_route_permute(x, w_gate, k, eps, bufs.h, bufs.logits, bufs.idx, bufs.w,
-                                   bufs.perm_out, stream=stream)
-            _, offsets, _, inv_perm, xg = bufs.perm_out
+        rs = bufs.sets[li & 1]
+        if fused_gate and seam and li > 0:
+            prev = bufs.sets[(li - 1) & 1]
+            nxt = bufs.x_alt if cur is x else x
+            moe_combine_norm_route_permute(bufs.yg, prev["perm_out"][3], prev["w"], cur, nxt,
+                                           w_gate, k, eps, bufs.h, bufs.logits, rs["idx"],
+                                           rs["w"], rs["perm_out"], stream=stream)
+            cur = nxt
+            _, offsets, _, inv_perm, xg = rs["perm_out"]
+        elif fused_gate:
+            moe_norm_route_permute(cur, w_gate, k, eps, bufs.h, bufs.logits, rs["idx"], rs["w"],
+                                   rs["perm_out"], stream=stream)
+            _, offsets, _, inv_perm, xg = rs["perm_out"]
         else:
-            moe_rmsnorm(x, eps, bufs.h, stream=stream)
+            moe_rmsnorm(cur, eps, bufs.h, stream=stream)
             moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
-            moe_route(bufs.logits, k, bufs.idx, bufs.w, stream=stream)
-            _, offsets, _, inv_perm, xg = moe_permute(bufs.idx, W.E, bufs.h, out=bufs.perm_out,
+            moe_route(bufs.logits, k, rs["idx"], rs["w"], stream=stream)
+            _, offsets, _, inv_perm, xg = moe_permute(rs["idx"], W.E, bufs.h, out=rs["perm_out"],
                                                       stream=stream)
         if logits_out is not None:
             logits_out.append(bufs.logits.clone())
         if idx_out is not None:
-            idx_out.append(bufs.idx.clone())
+            idx_out.append(rs["idx"].clone())
         if on_layer is not None:
             on_layer(li)
         moe_expert_ffn(W, xg, offsets, workspace=bufs.ws, yg=bufs.yg, stream=stream)
+        if seam and li + 1 < len(layers):
+            continue  # folded into the next block's front end
         if fused:
-            moe_combine_residual(bufs.yg, inv_perm, bufs.w, x, stream=stream)
+            moe_combine_residual(bufs.yg, inv_perm, rs["w"], cur, stream=stream)
         else:
-            moe_combine(bufs.yg, inv_perm, bufs.w, bufs.y, stream=stream)
-            moe_residual_add(x, bufs.y, stream=stream)
+            moe_combine(bufs.yg, inv_perm, rs["w"], bufs.y, stream=stream)
+            moe_residual_add(cur, bufs.y, stream=stream)
+    if cur is not x:
+        x.copy_(cur)
     return x

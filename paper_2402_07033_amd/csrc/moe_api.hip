@@ -162,7 +162,8 @@ int moe_route_permute(const float* logits, int T, int E, int k, const float* x, 
     if (!moe_aligned16(x) || !moe_aligned16(xg)) return MOE_ERR_INVALID_ARG;
     if (T < 1 || T > 16 || E > 16) return MOE_ERR_UNSUPPORTED;
     return moe_gate_small_launch(false, x, nullptr, logits, T, d, E, k, 0.f, nullptr, nullptr, idx,
-                                 weights, counts, offsets, perm, inv_perm, xg, (hipStream_t)stream);
+                                 weights, counts, offsets, perm, inv_perm, xg, nullptr, nullptr, nullptr,
+                                 0, nullptr, (hipStream_t)stream);
 }
 
 int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, int E, int k,
@@ -176,7 +177,32 @@ int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, in
     if (!moe_aligned16(x) || !moe_aligned16(xg) || !moe_aligned16(h)) return MOE_ERR_INVALID_ARG;
     if (T < 1 || T > 4 || E > 16) return MOE_ERR_UNSUPPORTED;
     return moe_gate_small_launch(true, x, w_gate, nullptr, T, d, E, k, eps, h, logits, idx, weights,
-                                 counts, offsets, perm, inv_perm, xg, (hipStream_t)stream);
+                                 counts, offsets, perm, inv_perm, xg, nullptr, nullptr, nullptr, 0,
+                                 nullptr, (hipStream_t)stream);
+}
+
+int moe_combine_norm_route_permute(const float* yg_prev, const int32_t* inv_perm_prev,
+                                   const float* weights_prev, int k_prev, const float* x_in,
+                                   float* x_out, const float* w_gate, int T, int d, int E, int k,
+                                   float eps, float* h, float* logits, int32_t* idx, float* weights,
+                                   int32_t* counts, int32_t* offsets, int32_t* perm,
+                                   int32_t* inv_perm, float* xg, void* stream) {
+    if (!tek_ok(T, E, k) || !dims_ok(d) || !(eps >= 0.f) || k_prev < 1 || k_prev > MOE_MAX_K)
+        return MOE_ERR_INVALID_ARG;
+    if (!yg_prev || !inv_perm_prev || !weights_prev || !x_in || !x_out || !w_gate || !h || !logits ||
+        !idx || !weights || !counts || !offsets || !perm || !inv_perm || !xg)
+        return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(x_in) || !moe_aligned16(x_out) || !moe_aligned16(xg) || !moe_aligned16(h) ||
+        !moe_aligned16(yg_prev))
+        return MOE_ERR_INVALID_ARG;
+    // every workgroup reads the inputs while workgroup 0 writes the outputs
+    if (x_out == x_in || (const int32_t*)inv_perm == inv_perm_prev ||
+        (const float*)weights == weights_prev || (const float*)xg == yg_prev)
+        return MOE_ERR_INVALID_ARG;
+    if (T < 1 || T > 4 || E > 16) return MOE_ERR_UNSUPPORTED;
+    return moe_gate_small_launch(true, x_in, w_gate, nullptr, T, d, E, k, eps, h, logits, idx,
+                                 weights, counts, offsets, perm, inv_perm, xg, yg_prev,
+                                 inv_perm_prev, weights_prev, k_prev, x_out, (hipStream_t)stream);
 }
 
 int moe_combine_residual(const float* yg, const int32_t* inv_perm, const float* weights, int T,

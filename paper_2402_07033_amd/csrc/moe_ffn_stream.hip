@@ -250,16 +250,32 @@ size_t moe_ffn_stream_workspace(int N, int E, int d, int f) {
     return (size_t)N * f * sizeof(float);
 }
 
+// Launches the instantiation for KSW with as many workgroups per CU as fit (kernels with
+// short per-wave reductions use few registers; several resident workgroups then keep
+// enough loads in flight per CU).  The work ranges are equal whatever the grid size.
 template <int NMAT, bool ACT_BF16>
-static int stream_dispatch(int KSW, dim3 grid, dim3 block, hipStream_t s, const StreamArgs& a) {
+static int stream_dispatch(int KSW, int waves, hipStream_t s, const StreamArgs& a) {
+    const void* fn = nullptr;
+    int slot = 0;
     switch (KSW) {
-        case 1: hipLaunchKernelGGL((stream_kernel<1, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
-        case 2: hipLaunchKernelGGL((stream_kernel<2, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
-        case 4: hipLaunchKernelGGL((stream_kernel<4, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
-        case 8: hipLaunchKernelGGL((stream_kernel<8, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
-        case 16: hipLaunchKernelGGL((stream_kernel<16, NMAT, ACT_BF16>), grid, block, 0, s, a); break;
+        case 1: fn = (const void*)stream_kernel<1, NMAT, ACT_BF16>; slot = 0; break;
+        case 2: fn = (const void*)stream_kernel<2, NMAT, ACT_BF16>; slot = 1; break;
+        case 4: fn = (const void*)stream_kernel<4, NMAT, ACT_BF16>; slot = 2; break;
+        case 8: fn = (const void*)stream_kernel<8, NMAT, ACT_BF16>; slot = 3; break;
+        case 16: fn = (const void*)stream_kernel<16, NMAT, ACT_BF16>; slot = 4; break;
         default: return MOE_ERR_UNSUPPORTED;
     }
+    static int occ_cache[5][ST_MAX_WAVES + 1];  // per instantiation: 0 = not asked yet
+    int occ = occ_cache[slot][waves];
+    if (occ == 0) {
+        MOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, 64 * waves, 0));
+        occ = occ < 1 ? 1 : (occ > 4 ? 4 : occ);
+        occ_cache[slot][waves] = occ;
+    }
+    StreamArgs args = a;
+    void* params[1] = {(void*)&args};
+    MOE_HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)(moe_num_cus() * occ)), dim3(64 * waves), params,
+                                0, s));
     return moe_launch_status();
 }
 
@@ -271,8 +287,6 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
     if (!stream_pick(d / 32, false, Wu, KSWu, Pu) || !stream_pick(f / 32, true, Wd, KSWd, Pd))
         return MOE_ERR_UNSUPPORTED;
     float* h = (float*)ws;
-    const unsigned grid = (unsigned)moe_num_cus();
-
     StreamArgs up;
     up.wfrag = (const u32x4_t*)W->w13;
     up.act = xg;
@@ -283,8 +297,8 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
     up.E = E; up.N = N; up.K = d; up.C = f;
     up.NB = f / 16; up.KS = d / 32; up.P = 1; up.W = Wu;
     int rc = (act_dtype == MOE_BF16)
-                 ? stream_dispatch<2, true>(KSWu, dim3(grid), dim3(64 * Wu), s, up)
-                 : stream_dispatch<2, false>(KSWu, dim3(grid), dim3(64 * Wu), s, up);
+                 ? stream_dispatch<2, true>(KSWu, Wu, s, up)
+                 : stream_dispatch<2, false>(KSWu, Wu, s, up);
     if (rc != MOE_OK) return rc;
     moe_record_mid_event(s);
 
@@ -297,5 +311,5 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
     dn.zero_n4 = 0;
     dn.E = E; dn.N = N; dn.K = f; dn.C = d;
     dn.NB = d / 16; dn.KS = f / 32; dn.P = Pd; dn.W = Wd;
-    return stream_dispatch<1, false>(KSWd, dim3(grid), dim3(64 * Wd), s, dn);
+    return stream_dispatch<1, false>(KSWd, Wd, s, dn);
 }

@@ -110,6 +110,8 @@ int moe_weights_free_impl(moe_weights* W);
 int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const float* logits_in,
                           int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
                           int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
-                          int32_t* perm, int32_t* inv_perm, float* xg, hipStream_t s);
+                          int32_t* perm, int32_t* inv_perm, float* xg, const float* yg_prev,
+                          const int32_t* inv_perm_prev, const float* weights_prev, int k_prev,
+                          float* x_out, hipStream_t s);
 int moe_combine_residual_launch(const float* yg, const int32_t* inv_perm, const float* weights, int T,
                                 int k, int d, float* x, hipStream_t s);

@@ -166,6 +166,47 @@ __device__ void permute_indices(const int32_t* __restrict__ idx, int N, int E,
     }
 }
 
+// The same batching for N <= 64 slots by one wavefront, without workgroup barriers: lane p
+// owns slot p; a ballot per expert gives the expert's count and every lane's rank among
+// the lanes of its expert.  The caller's next barrier publishes s_pos.
+__device__ __forceinline__ void permute_indices_wave(const int* __restrict__ s_idx, int N, int E,
+                                                     int32_t* __restrict__ counts,
+                                                     int32_t* __restrict__ offsets,
+                                                     int32_t* __restrict__ perm,
+                                                     int32_t* __restrict__ inv_perm, bool write,
+                                                     int* s_pos) {
+    const int lane = threadIdx.x & 63;
+    int e = -1;
+    if (lane < N) {
+        e = s_idx[lane];
+        e = e < 0 ? 0 : (e >= E ? E - 1 : e);
+    }
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int run = 0, pos = 0, my_cnt = 0, my_off = 0;
+    for (int ee = 0; ee < E; ee++) {
+        const unsigned long long m = __ballot(e == ee);
+        const int c = __popcll(m);
+        if (e == ee) pos = run + __popcll(m & below);
+        if (lane == ee) {
+            my_cnt = c;
+            my_off = run;
+        }
+        run += c;
+    }
+    if (lane == E) my_off = run;
+    if (lane < N) {
+        s_pos[lane] = pos;
+        if (write) {
+            perm[pos] = lane;
+            inv_perm[lane] = pos;
+        }
+    }
+    if (write) {
+        if (lane < E) counts[lane] = my_cnt;
+        if (lane <= E) offsets[lane] = my_off;
+    }
+}
+
 // N <= 1024: one launch does everything.  Every workgroup computes the slot
 // positions in LDS, workgroup 0 writes the index outputs, and the workgroups
 // share the row gather (16-byte chunks, coalesced along d).
@@ -362,14 +403,107 @@ int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t 
 #define GATE_MAX_T 16       // tokens the fused gate handles
 #define GATE_NORM_MAX_T 4   // ... when it also normalises and computes the router logits
 #define GATE_MAX_E 16
+// Partial sums of one thread for the fused RMSNorm + router: rows r = tid + i * PERM_THREADS.
+// TT = tokens handled (compile-time bound on T), UNR = rows whose loads are in flight together.
+// The pending combine + residual of the block before (COMB): the row values are
+//   x[t,r] + sum_j w_prev[t,j] * yg_prev[pos_prev[t,j], r]
+// in the arithmetic of combine_residual_kernel.
+struct GatePrev {
+    const float* yg;   // [N_prev, d] (global)
+    const int* pos;    // [T * k] rows of yg (inv_perm of the block before)
+    const float* w;    // [T * k] gate weights of the block before
+    int k;
+};
 
-template <bool NORM>
+template <int TT, int UNR, int KJMAX>
+__device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
+                                                  const float* __restrict__ w_gate, int T, int d,
+                                                  int E, int tid, const GatePrev& pv,
+                                                  float (&ss)[GATE_NORM_MAX_T],
+                                                  float (&acc)[GATE_NORM_MAX_T][GATE_MAX_E]) {
+    constexpr bool COMB = KJMAX > 0;        // KJMAX: compile-time bound on pv.k (0: no combine)
+    constexpr int KJ = COMB ? KJMAX : 1;
+    const bool vec = (E & 3) == 0;  // rows of w_gate are then 16-byte aligned
+    for (int r0 = tid; r0 < d; r0 += UNR * PERM_THREADS) {
+        float wr[UNR][GATE_MAX_E], xv[UNR][TT], yv[UNR][TT][KJ];
+#pragma unroll
+        for (int u = 0; u < UNR; u++) {
+            const int r = r0 + u * PERM_THREADS;
+#pragma unroll
+            for (int e = 0; e < GATE_MAX_E; e++) wr[u][e] = 0.f;
+#pragma unroll
+            for (int t = 0; t < TT; t++) {
+                xv[u][t] = 0.f;
+#pragma unroll
+                for (int j = 0; j < KJ; j++) yv[u][t][j] = 0.f;
+            }
+            if (r < d) {
+                if (vec) {
+#pragma unroll
+                    for (int q = 0; q < GATE_MAX_E / 4; q++) {
+                        if (4 * q < E) {
+                            const float4 v = *(const float4*)(w_gate + (size_t)r * E + 4 * q);
+                            wr[u][4 * q] = v.x; wr[u][4 * q + 1] = v.y;
+                            wr[u][4 * q + 2] = v.z; wr[u][4 * q + 3] = v.w;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < GATE_MAX_E; e++)
+                        if (e < E) wr[u][e] = w_gate[(size_t)r * E + e];
+                }
+#pragma unroll
+                for (int t = 0; t < TT; t++) {
+                    if (t < T) {
+                        xv[u][t] = x[(size_t)t * d + r];
+                        if (COMB) {
+#pragma unroll
+                            for (int j = 0; j < KJ; j++)
+                                if (j < pv.k) yv[u][t][j] = pv.yg[(size_t)pv.pos[t * pv.k + j] * d + r];
+                        }
+                    }
+                }
+            }
+        }
+        if (COMB) {
+#pragma unroll
+            for (int u = 0; u < UNR; u++) {
+#pragma unroll
+                for (int t = 0; t < TT; t++) {
+                    if (t < T) {
+                        float a = 0.f;
+#pragma unroll
+                        for (int j = 0; j < KJ; j++)
+                            if (j < pv.k) a += pv.w[t * pv.k + j] * yv[u][t][j];
+                        xv[u][t] += a;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; u++) {
+#pragma unroll
+            for (int t = 0; t < TT; t++) {
+                ss[t] = fmaf(xv[u][t], xv[u][t], ss[t]);
+#pragma unroll
+                for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = fmaf(xv[u][t], wr[u][e], acc[t][e]);
+            }
+        }
+    }
+}
+
+
+template <bool NORM, int KJMAX>
 __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
     const float* __restrict__ x, const float* __restrict__ w_gate, const float* __restrict__ logits_in,
     int T, int d, int E, int k, float eps, float* __restrict__ h_out, float* __restrict__ logits_out,
     int32_t* __restrict__ idx, float* __restrict__ weights, int32_t* __restrict__ counts,
     int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
-    float* __restrict__ xg) {
+    float* __restrict__ xg, const float* __restrict__ yg_prev,
+    const int32_t* __restrict__ inv_perm_prev, const float* __restrict__ weights_prev, int k_prev,
+    float* __restrict__ x_out) {
+    __shared__ int s_ppos[GATE_NORM_MAX_T * MOE_MAX_K];
+    __shared__ float s_pw[GATE_NORM_MAX_T * MOE_MAX_K];
     __shared__ int s_cnt[MOE_MAX_E];
     __shared__ int s_off[MOE_MAX_E + 1];
     __shared__ int s_wave[PERM_WAVES * MOE_MAX_E];
@@ -379,7 +513,17 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
     __shared__ float s_inv[GATE_MAX_T];
     __shared__ float s_part[PERM_WAVES][GATE_NORM_MAX_T * (GATE_MAX_E + 1)];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr bool COMB = KJMAX > 0;
     const bool writer = (blockIdx.x == 0);
+    // The partial sums read the previous block's positions and weights straight from
+    // global memory (uniform addresses), so that their other loads need not wait for a
+    // barrier; the LDS copies serve the row phase at the end and are published by the
+    // barriers in between.
+    GatePrev pv = {yg_prev, inv_perm_prev, weights_prev, k_prev};
+    if (COMB && tid < T * k_prev) {
+        s_ppos[tid] = inv_perm_prev[tid];
+        s_pw[tid] = weights_prev[tid];
+    }
 
     if (NORM) {
         // T <= GATE_NORM_MAX_T here.  Per thread: rows r = tid, tid+1024, ...; partial sums
@@ -391,20 +535,14 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
 #pragma unroll
             for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = 0.f;
         }
-        for (int r = tid; r < d; r += PERM_THREADS) {
-            float wr[GATE_MAX_E];
-#pragma unroll
-            for (int e = 0; e < GATE_MAX_E; e++) wr[e] = (e < E) ? w_gate[(size_t)r * E + e] : 0.f;
-#pragma unroll
-            for (int t = 0; t < GATE_NORM_MAX_T; t++) {
-                if (t < T) {
-                    const float xv = x[(size_t)t * d + r];
-                    ss[t] = fmaf(xv, xv, ss[t]);
-#pragma unroll
-                    for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = fmaf(xv, wr[e], acc[t][e]);
-                }
-            }
-        }
+        // The router matrix is cold in HBM at every layer: all loads of a group of rows
+        // are issued before the first use, so a thread pays the memory latency once per
+        // group instead of once per row (4 rows per group for one token, else 2).
+        if (T == 1)
+            gate_partial_sums<1, (KJMAX > 2 ? 2 : 4), KJMAX>(x, w_gate, T, d, E, tid, pv, ss, acc);
+        else
+            gate_partial_sums<GATE_NORM_MAX_T, (COMB ? 1 : 2), KJMAX>(x, w_gate, T, d, E, tid, pv,
+                                                                       ss, acc);
         // wave reduce, then across the 16 waves through LDS
 #pragma unroll
         for (int t = 0; t < GATE_NORM_MAX_T; t++) {
@@ -505,17 +643,37 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
 
     // ---- per-expert batching on the LDS copy of idx, then the row gather ----
     const int N = T * k;
-    permute_indices(s_idx, N, E, counts, offsets, perm, inv_perm, writer, s_cnt, s_off, s_wave,
-                    s_pos);
+    if (N <= 64) {
+        if (wave == 0) permute_indices_wave(s_idx, N, E, counts, offsets, perm, inv_perm, writer, s_pos);
+    } else {
+        permute_indices(s_idx, N, E, counts, offsets, perm, inv_perm, writer, s_cnt, s_off, s_wave,
+                        s_pos);
+    }
     __syncthreads();
     const int row_chunks = d / 4;
+    // row chunk c of token t, with the pending combine + residual applied
+    auto x_chunk = [&](int t, int c) -> float4 {
+        float4 r = ((const float4*)(x + (size_t)t * d))[c];
+        if (COMB) {
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j = 0; j < k_prev; j++) {
+                const float w = s_pw[t * k_prev + j];
+                const float4 v = ((const float4*)(yg_prev + (size_t)s_ppos[t * k_prev + j] * d))[c];
+                a.x += w * v.x;
+                a.y += w * v.y;
+                a.z += w * v.z;
+                a.w += w * v.w;
+            }
+            r.x += a.x; r.y += a.y; r.z += a.z; r.w += a.w;
+        }
+        return r;
+    };
     for (int p = blockIdx.x; p < N; p += gridDim.x) {
         const int t = p / k;
-        const float4* src = (const float4*)(x + (size_t)t * d);
         float4* dst = (float4*)(xg + (size_t)s_pos[p] * d);
         const float sc = NORM ? s_inv[t] : 1.0f;
         for (int c = tid; c < row_chunks; c += PERM_THREADS) {
-            float4 v = src[c];
+            float4 v = x_chunk(t, c);
             if (NORM) {
                 v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
             }
@@ -525,8 +683,12 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
     if (NORM && writer) {
         for (int t = 0; t < T; t++) {
             const float sc = s_inv[t];
-            for (int r = tid; r < d; r += PERM_THREADS)
-                h_out[(size_t)t * d + r] = x[(size_t)t * d + r] * sc;
+            for (int c = tid; c < row_chunks; c += PERM_THREADS) {
+                float4 v = x_chunk(t, c);
+                if (COMB) ((float4*)(x_out + (size_t)t * d))[c] = v;
+                v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+                ((float4*)(h_out + (size_t)t * d))[c] = v;
+            }
         }
     }
 }
@@ -534,17 +696,23 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
 int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const float* logits_in,
                           int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
                           int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
-                          int32_t* perm, int32_t* inv_perm, float* xg, hipStream_t s) {
+                          int32_t* perm, int32_t* inv_perm, float* xg, const float* yg_prev,
+                          const int32_t* inv_perm_prev, const float* weights_prev, int k_prev,
+                          float* x_out, hipStream_t s) {
     const int N = T * k;
     const unsigned grid = (unsigned)(N < 32 ? N : 32);
-    if (norm)
-        hipLaunchKernelGGL(gate_small_kernel<true>, dim3(grid), dim3(PERM_THREADS), 0, s, x, w_gate,
-                           logits_in, T, d, E, k, eps, h_out, logits_out, idx, weights, counts,
-                           offsets, perm, inv_perm, xg);
-    else
-        hipLaunchKernelGGL(gate_small_kernel<false>, dim3(grid), dim3(PERM_THREADS), 0, s, x, w_gate,
-                           logits_in, T, d, E, k, eps, h_out, logits_out, idx, weights, counts,
-                           offsets, perm, inv_perm, xg);
+    const bool comb = (yg_prev != nullptr);
+    if (comb && !norm) return MOE_ERR_INVALID_ARG;
+#define GATE_LAUNCH(NORM, KJMAX)                                                                  \
+    hipLaunchKernelGGL((gate_small_kernel<NORM, KJMAX>), dim3(grid), dim3(PERM_THREADS), 0, s, x, \
+                       w_gate, logits_in, T, d, E, k, eps, h_out, logits_out, idx, weights,      \
+                       counts, offsets, perm, inv_perm, xg, yg_prev, inv_perm_prev,              \
+                       weights_prev, k_prev, x_out)
+    if (comb && k_prev <= 2) GATE_LAUNCH(true, 2);
+    else if (comb) GATE_LAUNCH(true, MOE_MAX_K);
+    else if (norm) GATE_LAUNCH(true, 0);
+    else GATE_LAUNCH(false, 0);
+#undef GATE_LAUNCH
     return moe_launch_status();
 }
 

@@ -100,6 +100,81 @@ def test_fused_front_ends_match_separate_calls(moe):
     assert torch.equal(xa, xb)
 
 
+@pytest.mark.parametrize("T,E,k,k_prev,d", [(1, 8, 2, 2, 4096), (1, 16, 2, 2, 4096), (2, 8, 2, 3, 512),
+                                            (4, 6, 3, 2, 256), (3, 16, 8, 8, 4096)])
+def test_seam_call_matches_separate_calls(moe, T, E, k, k_prev, d):
+    """moe_combine_norm_route_permute == moe_combine_residual followed by
+    moe_norm_route_permute, bit for bit (same fp32 arithmetic)."""
+    rng = np.random.default_rng(100 * T + E + k)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    wg = to_dev((rng.standard_normal((d, E)) / np.sqrt(d)).astype(np.float32))
+    Np, N = T * k_prev, T * k
+    yg = to_dev(rng.standard_normal((Np + 3, d)).astype(np.float32))
+    inv = to_dev(rng.permutation(Np + 3)[:Np].astype(np.int32))
+    wp = to_dev(rng.random((T, k_prev)).astype(np.float32))
+    x0 = (rng.standard_normal((T, d)) * 1.5).astype(np.float32)
+
+    def outs():
+        return (torch.zeros(E, **i32), torch.zeros(E + 1, **i32), torch.zeros(N, **i32),
+                torch.zeros(N, **i32), torch.zeros((N, d), device="cuda"))
+
+    def small():
+        return (torch.zeros((T, d), device="cuda"), torch.zeros((T, E), device="cuda"),
+                torch.zeros((T, k), **i32), torch.zeros((T, k), device="cuda"))
+
+    # separate calls
+    xa = to_dev(x0.copy())
+    moe.moe_combine_residual(yg, inv, wp, xa)
+    ha, la, ia, wa = small()
+    oa = outs()
+    moe.moe_norm_route_permute(xa, wg, k, 1e-5, ha, la, ia, wa, oa)
+    # one launch
+    xin, xout = to_dev(x0.copy()), torch.zeros((T, d), device="cuda")
+    hb, lb, ib, wb = small()
+    ob = outs()
+    moe.moe_combine_norm_route_permute(yg, inv, wp, xin, xout, wg, k, 1e-5, hb, lb, ib, wb, ob)
+    torch.cuda.synchronize()
+    assert torch.equal(xin, to_dev(x0))  # the input stream is left alone
+    assert torch.equal(xout, xa)
+    assert torch.equal(hb, ha) and torch.equal(lb, la)
+    assert torch.equal(ib, ia) and torch.equal(wb, wa)
+    for a, b in zip(oa, ob):
+        assert torch.equal(a, b)
+    # aliasing the previous block's buffers is refused
+    with pytest.raises(moe.MoeError):
+        moe.moe_combine_norm_route_permute(yg, inv, wp, xin, xin, wg, k, 1e-5, hb, lb, ib, wb, ob)
+    if k == k_prev:
+        with pytest.raises(moe.MoeError):
+            moe.moe_combine_norm_route_permute(yg, ob[3], wb, xin, xout, wg, k, 1e-5, hb, lb, ib,
+                                               wb, ob)
+
+
+def test_stack_seam_on_off_identical(moe):
+    """The stack with the combine folded into the next front end gives the same bits as
+    with the separate combine+residual launches."""
+    T, L, k = 1, 5, 2
+    cfgs = [mi.small_config(f"m{l}", T, 512, 1024, 8, k, 4100 + l, w_dtype=mi.BF16) for l in range(L)]
+    layers = []
+    for cfg in cfgs:
+        w1, w3, w2 = mi.make_weights(cfg, threads=8)
+        w_gate = mi.normal_f32(cfg.seed, 1, (cfg.d, cfg.E), cfg.d ** -0.5)
+        layers.append((pack_layer(mi.LayerInputs(cfg, None, None, w1, w3, w2, w_gate)),
+                       to_dev(w_gate)))
+    x0 = mi.normal_f32(4100, 0, (T, 512))
+    res = []
+    for seam in (True, False):
+        xd = to_dev(x0.copy())
+        idx = []
+        moe.moe_stack_forward(layers, xd, k, idx_out=idx, seam=seam)
+        torch.cuda.synchronize()
+        res.append((to_host(xd), [to_host(i) for i in idx]))
+    assert (res[0][0] == res[1][0]).all()
+    for a, b in zip(res[0][1], res[1][1]):
+        assert (a == b).all()
+    for W, _ in layers:
+        W.free()
+
+
 def _run_stack(moe, cfgs, T, k, fused=True):
     """cfgs: one MoEConfig per layer.  Returns (gpu final x, oracle result, info)."""
     host_layers, dev_layers = [], []
