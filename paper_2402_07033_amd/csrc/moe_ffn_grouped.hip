@@ -45,7 +45,16 @@
 #define GG_FROWS 16        // weight fragment rows per workgroup tile (256 features)
 #define GG_THREADS 256
 #define GG_NS 8            // LDS stages of 16 B fragments (16 KiB each)
-#define GG_PA 4            // depth of the weight-fragment register ring (steps)
+// The weight fragments of step k are requested LA steps earlier into a register ring that
+// is named statically, so the step loop is unrolled U times (LA < U, reduction % U == 0).
+// Two variants: U = 4, LA = 3 (the default) and U = 8, LA = 5 with the matrix instructions
+// of empty row quarters skipped, for launches with few rows per expert, which are bound by
+// the weight stream from HBM and gain from more bytes in flight (5 is what the 8 LDS
+// stages allow, see the waits in the step).
+#define GG_U_MIN 4
+#ifndef GG_RAGGED_VARIANT
+#define GG_RAGGED_VARIANT 1
+#endif
 #define GG_VMEM_PER_STEP 8 // vector-memory requests per wave and step (4 B + 4 A)
 
 // ---- segment bookkeeping: expert e owns blocks [bbase_e, bbase_e + ceil(M_e/16)) ----
@@ -187,11 +196,62 @@ __device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offse
     return false;
 }
 
+// Cut points of the left-over tiles' joint reduction (S = R tiles x KS steps) for the
+// workgroups of one XCD: workgroup j covers [cut(j), cut(j+1)).  Pieces are multiples of
+// `unit` steps (KS is one too) and no piece is shorter than 8 steps.
+__device__ __forceinline__ int gg_piece_cut(int j, int S, int KS, int wgs, int unit) {
+    int per = ((S + wgs - 1) / wgs + unit - 1) / unit * unit;
+    per = per < 32 ? 32 : per;
+    const int c = j * per;
+    if (c >= S) return S;
+    const int r = c % KS;
+    if (r < 8) return c - r;
+    if (KS - r < 8) return c + (KS - r);
+    return c;
+}
+
 // MFMA with the accumulator pinned to the accumulation registers: 256 of them
 // are live per wave, and left to itself the register allocator shuffles them
 // through the vector registers inside the loop.
 __device__ __forceinline__ void gg_mfma(f32x4_t& c, const u32x4_t& a, const bf16x8_t& b) {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+// The 16 MFMAs of four token blocks (one quarter of the tile's rows), skipped as a whole
+// when those blocks lie beyond the last occupied one (quad >= nquads).  The branch sits
+// inside the asm statement so that the compiler keeps seeing one straight-line step: with
+// a branch of its own around matrix instructions it drains every counter at the borders.
+__device__ __forceinline__ void gg_mfma_quad(f32x4_t (&c0)[4], f32x4_t (&c1)[4], f32x4_t (&c2)[4],
+                                             f32x4_t (&c3)[4], const u32x4_t (&a)[4],
+                                             const bf16x8_t& b0, const bf16x8_t& b1,
+                                             const bf16x8_t& b2, const bf16x8_t& b3, int nquads,
+                                             const int quad) {
+    asm volatile(
+        "s_cmp_gt_i32 %24, %25\n\t"
+        "s_cbranch_scc0 1f\n\t"
+        "v_mfma_f32_16x16x32_bf16 %0, %16, %20, %0\n\t"
+        "v_mfma_f32_16x16x32_bf16 %1, %17, %20, %1\n\t"
+        "v_mfma_f32_16x16x32_bf16 %2, %18, %20, %2\n\t"
+        "v_mfma_f32_16x16x32_bf16 %3, %19, %20, %3\n\t"
+        "v_mfma_f32_16x16x32_bf16 %4, %16, %21, %4\n\t"
+        "v_mfma_f32_16x16x32_bf16 %5, %17, %21, %5\n\t"
+        "v_mfma_f32_16x16x32_bf16 %6, %18, %21, %6\n\t"
+        "v_mfma_f32_16x16x32_bf16 %7, %19, %21, %7\n\t"
+        "v_mfma_f32_16x16x32_bf16 %8, %16, %22, %8\n\t"
+        "v_mfma_f32_16x16x32_bf16 %9, %17, %22, %9\n\t"
+        "v_mfma_f32_16x16x32_bf16 %10, %18, %22, %10\n\t"
+        "v_mfma_f32_16x16x32_bf16 %11, %19, %22, %11\n\t"
+        "v_mfma_f32_16x16x32_bf16 %12, %16, %23, %12\n\t"
+        "v_mfma_f32_16x16x32_bf16 %13, %17, %23, %13\n\t"
+        "v_mfma_f32_16x16x32_bf16 %14, %18, %23, %14\n\t"
+        "v_mfma_f32_16x16x32_bf16 %15, %19, %23, %15\n\t"
+        "1:"
+        : "+a"(c0[0]), "+a"(c0[1]), "+a"(c0[2]), "+a"(c0[3]), "+a"(c1[0]), "+a"(c1[1]),
+          "+a"(c1[2]), "+a"(c1[3]), "+a"(c2[0]), "+a"(c2[1]), "+a"(c2[2]), "+a"(c2[3]),
+          "+a"(c3[0]), "+a"(c3[1]), "+a"(c3[2]), "+a"(c3[3])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(b0), "v"(b1), "v"(b2), "v"(b3),
+          "s"(nquads), "i"(quad)
+        : "scc");
 }
 
 // Global source pointers of one tile for this wave (all wave-uniform).
@@ -214,7 +274,7 @@ __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo
     }
 }
 
-template <bool UP>
+template <bool UP, int U, int LA, bool SKIP>  // LA < U, LA <= GG_NS - 3
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][16 fragments][64 lanes]
@@ -244,17 +304,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     if (split) {
         const int R = chunk - n_full * wgs;
         const int S = R * a.KS;
-        int per = (((S + wgs - 1) / wgs) + 3) & ~3;
-        per = per < 32 ? 32 : per;
-        // cut points are snapped so that no piece is shorter than 8 steps
-        auto snap = [&](int c) -> int {
-            if (c >= S) return S;
-            const int r = c % a.KS;
-            if (r < 8) return c - r;
-            if (a.KS - r < 8) return c + (a.KS - r);
-            return c;
-        };
-        const int c0 = snap(me * per), c1 = snap((me + 1) * per);
+        const int c0 = gg_piece_cut(me, S, a.KS, wgs, U), c1 = gg_piece_cut(me + 1, S, a.KS, wgs, U);
         if (c0 < c1) {
             const int rA = c0 / a.KS;
             const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
@@ -312,7 +362,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     };
 
     f32x4_t acc[16][4];
-    u32x4_t areg[GG_PA][4];
+    u32x4_t areg[U][4];
     bf16x8_t breg[16];
 
     // ---- prologue of the first tile: request stages 0..NS-2 and A of steps 0..PA-2 ----
@@ -320,7 +370,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; i++) issue_b(i, j, j);
 #pragma unroll
-    for (int s = 0; s < GG_PA - 1; s++)
+    for (int s = 0; s < LA; s++)
 #pragma unroll
         for (int j = 0; j < 4; j++) areg[s][j] = *a_src(j, s);
     GG_WAIT_VMCNT(0);
@@ -339,31 +389,31 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         asm volatile("s_nop 7" ::: "memory");
 
         // One reduction step.  Ac: weight fragments of this step; An: ring slot that
-        // receives the fragments of step k+GG_PA-1.  fast: every look-ahead lies inside
+        // receives the fragments of step k+LA.  fast: every look-ahead lies inside
         // the current tile, so there is nothing to decide (compile-time after inlining).
+        // quarters of the tile's rows that hold tokens (SKIP: the others do no arithmetic)
+        const int nquads = __builtin_amdgcn_readfirstlane((cur.nblk + 3) >> 2);
         auto step = [&](int k, u32x4_t(&Ac)[4], u32x4_t(&An)[4], const bool fast) {
             // do the look-ahead requests exist (in this tile or the next one)?
             const bool la_b = fast || has_next || (k + GG_NS - 1 < KT);
-            const bool la_a = fast || has_next || (k + GG_PA - 1 < KT);
+            const bool la_a = fast || has_next || (k + LA < KT);
             const bool more = fast || has_next || (k + 1 < KT);
-            // Stage k+1 and the weights of step k were requested >= 2 steps ago; requests
-            // retire in order, so at most the last two steps' worth may still be in flight.
-            // Once the stream has ended (last tile, no look-ahead) wait for everything.
-            if (la_b) GG_WAIT_VMCNT((GG_PA - 2) * GG_VMEM_PER_STEP);
+            // The weights of step k were requested LA steps ago, after that step's requests
+            // for stage k+GG_NS-1-LA; requests retire in order, so with at most the last
+            // LA-1 steps' worth still in flight they have arrived, and so have the stages
+            // requested before them (LA <= GG_NS-3: up to stage k+2).  Once the stream has
+            // ended (last tile, no look-ahead) wait for everything.
+            if (la_b) GG_WAIT_VMCNT((LA - 1) * GG_VMEM_PER_STEP);
             else GG_WAIT_VMCNT(0);
-            // One barrier per TWO steps: at an even step every wave has waited for all its
-            // requests older than two steps, which covers its shares of stages k+1 and k+2
-            // (requested GG_NS-2 and GG_NS-3 steps ago), so both are published here; and the
+            // One barrier per TWO steps: at an even step every wave has waited for its
+            // shares of stages k+1 and k+2 (see above), so both are published here; and the
             // buffers refilled during steps k and k+1 (stages k-1 and k) were last read
             // before this barrier.
             if (more && (k & 1) == 0) __builtin_amdgcn_s_barrier();
             const u32x4_t* pb = lds + ((g + 1) % GG_NS) * 16 * 64 + lane;
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                // one vector-memory request per 8 MFMAs, so that the requests of the four
-                // waves never queue up in front of the matrix instructions
-                if ((i & 1) == 0) {
-                    const int v = i >> 1;
+            // request number v of this step: 0..3 = this wave's 4 blocks of stage k+GG_NS-1
+            // (straight into LDS), 4..7 = its 4 weight fragments of step k+LA
+            auto issue = [&](const int v) {
                     if (v < 4) {
                         if (fast) {
                             __builtin_amdgcn_global_load_lds(
@@ -378,32 +428,55 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
                     } else {
                         if (fast)
                             An[v - 4] = *(const u32x4_t*)((const char*)(scur.a[v - 4] +
-                                                          (size_t)(k + GG_PA - 1) * 64) + voff);
+                                                          (size_t)(k + LA) * 64) + voff);
                         else if (la_a)
-                            An[v - 4] = *a_src(v - 4, k + GG_PA - 1);
+                            An[v - 4] = *a_src(v - 4, k + LA);
                     }
-                    // LDS reads return in order: with at most 14 younger ones in flight,
-                    // breg[i] and breg[i+1] (refilled one step ago) have arrived
-                    GG_WAIT_LGKM(14);
-                }
+            };
+            if constexpr (!SKIP) {
 #pragma unroll
-                for (int j = 0; j < 4; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
-                if (more) breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
+                for (int i = 0; i < 16; i++) {
+                    // one vector-memory request per 8 MFMAs, so that the requests of the four
+                    // waves never queue up in front of the matrix instructions
+                    if ((i & 1) == 0) {
+                        issue(i >> 1);
+                        // LDS reads return in order: with at most 14 younger ones in flight,
+                        // breg[i] and breg[i+1] (refilled one step ago) have arrived
+                        GG_WAIT_LGKM(14);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
+                    if (more) breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    issue(2 * q);
+                    issue(2 * q + 1);
+                    // with at most 12 younger LDS reads in flight, breg[4q..4q+3] have arrived
+                    GG_WAIT_LGKM(12);
+                    gg_mfma_quad(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3], Ac,
+                                 breg[4 * q], breg[4 * q + 1], breg[4 * q + 2], breg[4 * q + 3],
+                                 nquads, q);
+                    if (more) {
+#pragma unroll
+                        for (int i = 4 * q; i < 4 * q + 4; i++)
+                            breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
+                    }
+                }
             }
             g++;
         };
         // steps whose look-aheads (k+GG_NS-1 at most) stay inside this tile: no conditions
-        const int k_fast = ((KT - GG_NS + 1) / GG_PA) * GG_PA;
+        const int k_fast = ((KT - GG_NS + 1) / U) * U;
         int k = 0;
-        for (; k < k_fast; k += GG_PA) {
+        for (; k < k_fast; k += U) {
 #pragma unroll
-            for (int u = 0; u < GG_PA; u++)
-                step(k + u, areg[u], areg[(u + GG_PA - 1) % GG_PA], true);
+            for (int u = 0; u < U; u++) step(k + u, areg[u], areg[(u + LA) % U], true);
         }
-        for (; k < KT; k += GG_PA) {
+        for (; k < KT; k += U) {
 #pragma unroll
-            for (int u = 0; u < GG_PA; u++)
-                step(k + u, areg[u], areg[(u + GG_PA - 1) % GG_PA], false);
+            for (int u = 0; u < U; u++) step(k + u, areg[u], areg[(u + LA) % U], false);
         }
 
         // ---- epilogue of the current tile (the next tile's loads are in flight) ----
@@ -467,7 +540,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
 // Adds the pieces of every left-over tile of the second projection into yg, in the order
 // of the workgroups that produced them (deterministic).  One workgroup per (XCD, left-over
 // tile); it recomputes the same cut points the GEMM workgroups used.
-__global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs) {
+__global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, int unit) {
     __shared__ int s_slot[80];
     __shared__ int s_n;
     const int xcd = blockIdx.x / wgs, r = blockIdx.x % wgs;
@@ -483,18 +556,9 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs) {
     if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + n_full * wgs + r, ti)) return;
     if (threadIdx.x == 0) {
         const int S = R * a.KS;
-        int per = (((S + wgs - 1) / wgs) + 3) & ~3;
-        per = per < 32 ? 32 : per;
-        auto snap = [&](int c) -> int {
-            if (c >= S) return S;
-            const int q = c % a.KS;
-            if (q < 8) return c - q;
-            if (a.KS - q < 8) return c + (a.KS - q);
-            return c;
-        };
         int n = 0;
         for (int j = 0; j < wgs; j++) {
-            const int c0 = snap(j * per), c1 = snap((j + 1) * per);
+            const int c0 = gg_piece_cut(j, S, a.KS, wgs, unit), c1 = gg_piece_cut(j + 1, S, a.KS, wgs, unit);
             if (c0 >= c1) continue;
             const int rA = c0 / a.KS;
             const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
@@ -540,21 +604,34 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     // down tile = 256 features: d % 256 == 0; both give reductions of >= 8 steps, step
     // counts that are multiples of 4.
     if (f % 128 != 0 || d % 256 != 0) return MOE_ERR_UNSUPPORTED;
-    // the step loop is unrolled by the register-ring depth and looks GG_NS-1 steps ahead
-    if ((d / 32) % GG_PA != 0 || (f / 32) % GG_PA != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
+    // the step loop is unrolled 4 or 8 times and looks GG_NS-1 steps ahead
+    if ((d / 32) % GG_U_MIN != 0 || (f / 32) % GG_U_MIN != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
         return MOE_ERR_UNSUPPORTED;
+    // Few rows per expert (at most 40 on average, i.e. tiles with one quarter occupied):
+    // the variant with the deeper weight ring that skips empty row quarters.  Measured on
+    // the Mixtral shape it is 5-10 % faster up to 32 rows per expert and 2-3 % slower from
+    // 64 rows on.
+    const bool ragged = GG_RAGGED_VARIANT && (long long)N <= (long long)E * 40;
+    const bool up8 = ragged && (d / 32) % 8 == 0, dn8 = ragged && (f / 32) % 8 == 0;
     const size_t nb = gg_max_blocks(N, E);
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
     const size_t lds_bytes = GG_NS * 16 * MOE_FRAG_BYTES;
     const unsigned pgrid = (unsigned)((moe_num_cus() + 7) / 8 * 8);  // persistent: one per CU
 
+    const void* k_up = up8 ? (const void*)gg_gemm_kernel<true, 8, 5, true>
+                           : (const void*)gg_gemm_kernel<true, 4, 3, false>;
+    const void* k_dn = dn8 ? (const void*)gg_gemm_kernel<false, 8, 5, true>
+                           : (const void*)gg_gemm_kernel<false, 4, 3, false>;
     static bool attr_set = false;
     if (!attr_set) {
-        MOE_HIP_TRY(hipFuncSetAttribute((const void*)gg_gemm_kernel<true>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        MOE_HIP_TRY(hipFuncSetAttribute((const void*)gg_gemm_kernel<false>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        const void* all[4] = {(const void*)gg_gemm_kernel<true, 8, 5, true>,
+                              (const void*)gg_gemm_kernel<true, 4, 3, false>,
+                              (const void*)gg_gemm_kernel<false, 8, 5, true>,
+                              (const void*)gg_gemm_kernel<false, 4, 3, false>};
+        for (int i = 0; i < 4; i++)
+            MOE_HIP_TRY(hipFuncSetAttribute(all[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)lds_bytes));
         attr_set = true;
     }
 
@@ -578,7 +655,10 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.C = 0;
     up.split = 0;
     up.part = nullptr;
-    hipLaunchKernelGGL(gg_gemm_kernel<true>, dim3(pgrid), dim3(GG_THREADS), lds_bytes, s, up);
+    {
+        void* params[1] = {(void*)&up};
+        MOE_HIP_TRY(hipLaunchKernel(k_up, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
+    }
     moe_record_mid_event(s);
 
     GroupedArgs dn;
@@ -597,8 +677,12 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.split = (f / 32 >= 64) ? 1 : 0;
     dn.part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
                        gg_align256(nb * 16 * f * 2));
-    hipLaunchKernelGGL(gg_gemm_kernel<false>, dim3(pgrid), dim3(GG_THREADS), lds_bytes, s, dn);
+    {
+        void* params[1] = {(void*)&dn};
+        MOE_HIP_TRY(hipLaunchKernel(k_dn, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
+    }
     if (dn.split)
-        hipLaunchKernelGGL(gg_fixup_kernel, dim3(pgrid), dim3(256), 0, s, dn, (int)(pgrid / 8));
+        hipLaunchKernelGGL(gg_fixup_kernel, dim3(pgrid), dim3(256), 0, s, dn, (int)(pgrid / 8),
+                           dn8 ? 8 : 4);
     return moe_launch_status();
 }

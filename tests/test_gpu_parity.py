@@ -160,7 +160,10 @@ def test_layer_bf16_stream_path(moe, T, d, f, E, k, xdt):
 
 @pytest.mark.parametrize("T,d,f,E,k,xdt", [
     (1, 256, 512, 8, 2, mi.F32), (100, 256, 512, 8, 2, mi.BF16), (600, 256, 384, 4, 2, mi.BF16),
-    (300, 512, 1024, 8, 2, mi.F32), (1100, 256, 256, 3, 1, mi.BF16)])
+    (300, 512, 1024, 8, 2, mi.F32), (1100, 256, 256, 3, 1, mi.BF16),
+    # few rows per expert: the deep-ring variant that skips empty row quarters; f = 384 keeps
+    # the second projection on the default variant, f = 2304 cuts its tiles along the reduction
+    (70, 256, 384, 8, 2, mi.F32), (150, 512, 2304, 8, 2, mi.BF16), (9, 256, 2048, 16, 2, mi.BF16)])
 def test_layer_bf16_grouped_path(moe, T, d, f, E, k, xdt):
     cfg = mi.small_config("gg", T, d, f, E, k, 600 + T + d, w_dtype=mi.BF16, x_dtype=xdt,
                           zipf_s=1.2)
