@@ -538,10 +538,12 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
 }
 
 // Adds the pieces of every left-over tile of the second projection into yg, in the order
-// of the workgroups that produced them (deterministic).  One workgroup per (XCD, left-over
-// tile); it recomputes the same cut points the GEMM workgroups used.
+// of the workgroups that produced them (deterministic).  blockIdx.x = (XCD, left-over
+// tile), blockIdx.y = group of 16 rows of the tile; every workgroup recomputes the cut
+// points the GEMM workgroups used.
+#define GG_FIX_ROWS 16
 __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, int unit) {
-    __shared__ int s_slot[80];
+    __shared__ int s_slot[64];
     __shared__ int s_n;
     const int xcd = blockIdx.x / wgs, r = blockIdx.x % wgs;
     const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
@@ -554,31 +556,60 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
     if (r >= R) return;
     TileInfo ti;
     if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + n_full * wgs + r, ti)) return;
-    if (threadIdx.x == 0) {
+    const int tile_rows = (ti.si.rows - ti.blk0 * 16) < 256 ? (ti.si.rows - ti.blk0 * 16) : 256;
+    const int row_lo = blockIdx.y * GG_FIX_ROWS;
+    if (row_lo >= tile_rows) return;
+    // lane j of the first wave looks at workgroup j's cut: it holds at most one piece of
+    // this tile; a ballot keeps the pieces in workgroup order (wgs <= 64)
+    if (threadIdx.x < 64) {
+        const int j = threadIdx.x;
         const int S = R * a.KS;
-        int n = 0;
-        for (int j = 0; j < wgs; j++) {
+        int slot = -1;
+        if (j < wgs) {
             const int c0 = gg_piece_cut(j, S, a.KS, wgs, unit), c1 = gg_piece_cut(j + 1, S, a.KS, wgs, unit);
-            if (c0 >= c1) continue;
-            const int rA = c0 / a.KS;
-            const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
-            if (rA == r && n < 80) s_slot[n++] = (xcd * wgs + j) * 2 + 0;
-            if (c1 > endA && rA + 1 == r && n < 80) s_slot[n++] = (xcd * wgs + j) * 2 + 1;
+            if (c0 < c1) {
+                const int rA = c0 / a.KS;
+                const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
+                if (rA == r) slot = (xcd * wgs + j) * 2 + 0;
+                else if (c1 > endA && rA + 1 == r) slot = (xcd * wgs + j) * 2 + 1;
+            }
         }
-        s_n = n;
+        const unsigned long long m = __ballot(slot >= 0);
+        const unsigned long long below = (j == 0) ? 0ull : (~0ull >> (64 - j));
+        if (slot >= 0) s_slot[__popcll(m & below)] = slot;
+        if (j == 0) s_n = __popcll(m);
     }
     __syncthreads();
     const int n = s_n;
-    const int rows = (ti.si.rows - ti.blk0 * 16) < 256 ? (ti.si.rows - ti.blk0 * 16) : 256;
-    for (int idx = threadIdx.x; idx < rows * 64; idx += 256) {
-        const int row = idx >> 6, c4 = idx & 63;
-        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int p = 0; p < n; p++) {
-            const float4 v = *(const float4*)(a.part + ((size_t)s_slot[p] * 256 + row) * 256 + c4 * 4);
-            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    const int rows = (tile_rows - row_lo) < GG_FIX_ROWS ? (tile_rows - row_lo) : GG_FIX_ROWS;
+    constexpr int IT = GG_FIX_ROWS * 64 / 256;  // float4 per thread
+    float4 sum[IT];
+    const float* src[IT];
+#pragma unroll
+    for (int it = 0; it < IT; it++) {
+        const int idx = it * 256 + threadIdx.x;
+        // rows past the end of the tile read row 0 of the group instead (never stored)
+        const int row = row_lo + ((idx >> 6) < rows ? (idx >> 6) : 0);
+        src[it] = a.part + (size_t)row * 256 + (idx & 63) * 4;
+        sum[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int p = 0; p < n; p++) {
+        const size_t base = (size_t)s_slot[p] * 256 * 256;
+        float4 v[IT];
+#pragma unroll
+        for (int it = 0; it < IT; it++) v[it] = *(const float4*)(src[it] + base);
+#pragma unroll
+        for (int it = 0; it < IT; it++) {
+            sum[it].x += v[it].x; sum[it].y += v[it].y; sum[it].z += v[it].z; sum[it].w += v[it].w;
         }
-        *(float4*)((float*)a.out + (size_t)(ti.si.row0 + ti.blk0 * 16 + row) * a.C +
-                   ti.nt * GG_FROWS * 16 + c4 * 4) = sum;
+    }
+#pragma unroll
+    for (int it = 0; it < IT; it++) {
+        const int idx = it * 256 + threadIdx.x;
+        if ((idx >> 6) < rows)
+            *(float4*)((float*)a.out +
+                       (size_t)(ti.si.row0 + ti.blk0 * 16 + row_lo + (idx >> 6)) * a.C +
+                       ti.nt * GG_FROWS * 16 + (idx & 63) * 4) = sum[it];
     }
 }
 
@@ -674,7 +705,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.C = d;
     // Cutting left-over tiles along the reduction needs pieces of >= 32 steps; the pieces
     // are stored in scratch behind hp and summed by gg_fixup_kernel.
-    dn.split = (f / 32 >= 64) ? 1 : 0;
+    dn.split = (f / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;  // the fix-up lists pieces with one wave
     dn.part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
                        gg_align256(nb * 16 * f * 2));
     {
@@ -682,7 +713,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
         MOE_HIP_TRY(hipLaunchKernel(k_dn, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
     }
     if (dn.split)
-        hipLaunchKernelGGL(gg_fixup_kernel, dim3(pgrid), dim3(256), 0, s, dn, (int)(pgrid / 8),
-                           dn8 ? 8 : 4);
+        hipLaunchKernelGGL(gg_fixup_kernel, dim3(pgrid, 256 / GG_FIX_ROWS), dim3(256), 0, s, dn,
+                           (int)(pgrid / 8), dn8 ? 8 : 4);
     return moe_launch_status();
 }
