@@ -132,8 +132,8 @@ struct GroupedArgs {
     int NT;      // workgroup tiles along the features = FR / GG_FROWS
     int KS_out;  // up: f/32 (fragment columns of hp); down: unused
     int C;       // down: d (row length of yg)
-    int split;   // down: deal the left-over tiles of each XCD in pieces of their reduction
-    float* part; // down, split: partial tiles [8 XCDs][workgroups per XCD][2][256][256] fp32
+    int split;   // deal the left-over tiles of each XCD in pieces of their reduction
+    float* part; // split: partial tiles [8 XCDs][workgroups per XCD][2][256][256] fp32
 };
 
 // s_waitcnt with only one counter constrained (gfx9 encoding: vmcnt = bits 3:0 and
@@ -274,7 +274,11 @@ __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo
     }
 }
 
-template <bool UP, int U, int LA, bool SKIP>  // LA < U, LA <= GG_NS - 3
+// MODE: which units of work a launch covers: 0 = whole tiles and pieces (second projection:
+// one epilogue serves both), 1 = whole tiles only, 2 = pieces only (the first projection
+// takes two launches, because an epilogue with both the SiLU*mul body and the raw store of
+// partial sums makes the compiler spill ~150 accumulators per tile).
+template <bool UP, int U, int LA, bool SKIP, int MODE>  // LA < U, LA <= GG_NS - 3
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][16 fragments][64 lanes]
@@ -286,10 +290,10 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     // This workgroup's units of work.  The logical tiles of XCD x are x*per_xcd ... ; the
     // 32 workgroups of an XCD take them round-robin (slot = id/8, id/8 + wgs, ...).  When
     // the tile count is not a multiple of the workgroup count the last round would leave
-    // most CUs idle (560 second-projection tiles over 256 CUs = 2.19 rounds), so for the
-    // second projection (linear in the reduction) the left-over tiles are cut along the
-    // reduction instead, in equal pieces for all workgroups; every piece stores its partial
-    // tile into scratch and gg_fixup_kernel adds the pieces of a tile in a fixed order.
+    // most CUs idle (576 second-projection tiles over 256 CUs = 2.25 rounds), so the
+    // left-over tiles are cut along the reduction instead, in equal pieces for all
+    // workgroups; every piece stores its partial sums into scratch and gg_fixup_kernel adds
+    // the pieces of a tile in a fixed order (then applies SiLU*mul, first projection).
     const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
     const int per_xcd = (total + 7) / 8;
     const int xcd = blockIdx.x & 7;
@@ -297,7 +301,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     const int me = blockIdx.x >> 3;
     int chunk = total - xcd * per_xcd;
     chunk = chunk < 0 ? 0 : (chunk > per_xcd ? per_xcd : chunk);  // tiles of this XCD
-    const bool split = !UP && a.split && (chunk % wgs) != 0;
+    const bool split = a.split && (chunk % wgs) != 0;
     const int n_full = split ? chunk / wgs : (chunk - me + wgs - 1) / wgs;  // whole tiles I own
     // pieces of the left-over tiles (slots n_full*wgs ... chunk-1) for this workgroup
     int pc_tile[2] = {0, 0}, pc_lo[2] = {0, 0}, pc_len[2] = {0, 0}, n_pieces = 0;
@@ -316,7 +320,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             }
         }
     }
-    const int n_units = n_full + n_pieces;
+    const int n_units = (MODE == 1) ? n_full : n_full + n_pieces;
     auto unit_at = [&](int n, TileInfo& ti) -> bool {
         if (n >= n_units) return false;
         int sl, lo = 0, len = a.KS;
@@ -330,12 +334,12 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + sl, ti)) return false;
         ti.k_lo = lo;
         ti.klen = len;
-        ti.partial = (len != a.KS);
+        ti.partial = (n >= n_full);  // pieces always go through scratch and the fix-up
         ti.piece = n < n_full ? 0 : n - n_full;
         return true;
     };
 
-    int unit = 0;
+    int unit = (MODE == 2) ? n_full : 0;
     TileInfo cur, nxt;
     if (!unit_at(unit, cur)) return;
     bool has_next = unit_at(unit + 1, nxt);
@@ -483,11 +487,24 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         // the compiler cannot see the MFMAs: cover the matrix-core write -> read hazard
         asm volatile("s_nop 15\n s_nop 15" ::: "memory");
         const int t = lane & 15, fq = lane >> 4;  // token in block, feature quad
+        if (UP && MODE == 2) {
+            // piece of a tile: raw partial sums to this workgroup's scratch slot; the fix-up
+            // kernel adds the pieces and applies SiLU*mul
+            float* slot = a.part + ((((size_t)xcd * wgs + me) * 2 + cur.piece) * 256 + t) * 256 +
+                          (4 * wave) * 16 + 4 * fq;
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            if (i >= cur.nblk) continue;
-            const int blk = cur.blk0 + i;  // block inside the segment
-            if (UP) {
+            for (int i = 0; i < 16; i++) {
+                if (i >= cur.nblk) continue;
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    *(float4*)(slot + (size_t)i * 16 * 256 + j * 16) =
+                        make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            }
+        } else if (UP) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                if (i >= cur.nblk) continue;
+                const int blk = cur.blk0 + i;  // block inside the segment
                 // fragment rows 4*wave+j: j even = w1 rows, j odd = w3 rows of the same columns
 #pragma unroll
                 for (int jj = 0; jj < 2; jj++) {
@@ -507,7 +524,12 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
                         (fq & 1) * 8;
                     *(uint2*)dst = pk;
                 }
-            } else {
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                if (i >= cur.nblk) continue;
+                const int blk = cur.blk0 + i;  // block inside the segment
                 // whole tiles go to yg; pieces of a tile to this workgroup's scratch slot
                 // (same code, only the destination differs)
                 const int r_in_seg = blk * 16 + t;
@@ -542,6 +564,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
 // tile), blockIdx.y = group of 16 rows of the tile; every workgroup recomputes the cut
 // points the GEMM workgroups used.
 #define GG_FIX_ROWS 16
+template <bool UP>
 __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, int unit) {
     __shared__ int s_slot[64];
     __shared__ int s_n;
@@ -556,7 +579,10 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
     if (r >= R) return;
     TileInfo ti;
     if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + n_full * wgs + r, ti)) return;
-    const int tile_rows = (ti.si.rows - ti.blk0 * 16) < 256 ? (ti.si.rows - ti.blk0 * 16) : 256;
+    // second projection: the tile's real rows; first: every row of its blocks (h is kept in
+    // whole 16-row fragments, padding rows included)
+    const int tile_rows = UP ? ti.nblk * 16
+                             : ((ti.si.rows - ti.blk0 * 16) < 256 ? (ti.si.rows - ti.blk0 * 16) : 256);
     const int row_lo = blockIdx.y * GG_FIX_ROWS;
     if (row_lo >= tile_rows) return;
     // lane j of the first wave looks at workgroup j's cut: it holds at most one piece of
@@ -582,34 +608,86 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
     __syncthreads();
     const int n = s_n;
     const int rows = (tile_rows - row_lo) < GG_FIX_ROWS ? (tile_rows - row_lo) : GG_FIX_ROWS;
-    constexpr int IT = GG_FIX_ROWS * 64 / 256;  // float4 per thread
-    float4 sum[IT];
-    const float* src[IT];
-#pragma unroll
-    for (int it = 0; it < IT; it++) {
-        const int idx = it * 256 + threadIdx.x;
-        // rows past the end of the tile read row 0 of the group instead (never stored)
-        const int row = row_lo + ((idx >> 6) < rows ? (idx >> 6) : 0);
-        src[it] = a.part + (size_t)row * 256 + (idx & 63) * 4;
-        sum[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    for (int p = 0; p < n; p++) {
-        const size_t base = (size_t)s_slot[p] * 256 * 256;
-        float4 v[IT];
-#pragma unroll
-        for (int it = 0; it < IT; it++) v[it] = *(const float4*)(src[it] + base);
+    if (UP) {
+        // item = (row, block of 16 h-columns cb, feature quad fq): a = x.w1 from fragment
+        // row 2cb, b = x.w3 from fragment row 2cb+1, four columns each
+        constexpr int IT = GG_FIX_ROWS * 32 / 256;
+        float4 sa[IT], sb[IT];
+        const float* src[IT];
 #pragma unroll
         for (int it = 0; it < IT; it++) {
-            sum[it].x += v[it].x; sum[it].y += v[it].y; sum[it].z += v[it].z; sum[it].w += v[it].w;
+            const int idx = it * 256 + threadIdx.x;
+            const int rr = (idx >> 5) < rows ? (idx >> 5) : 0, cb = (idx >> 2) & 7, fq = idx & 3;
+            src[it] = a.part + (size_t)(row_lo + rr) * 256 + (2 * cb) * 16 + 4 * fq;
+            sa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            sb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
-    }
+        for (int p = 0; p < n; p++) {
+            const size_t base = (size_t)s_slot[p] * 256 * 256;
+            float4 va[IT], vb[IT];
 #pragma unroll
-    for (int it = 0; it < IT; it++) {
-        const int idx = it * 256 + threadIdx.x;
-        if ((idx >> 6) < rows)
-            *(float4*)((float*)a.out +
-                       (size_t)(ti.si.row0 + ti.blk0 * 16 + row_lo + (idx >> 6)) * a.C +
-                       ti.nt * GG_FROWS * 16 + (idx & 63) * 4) = sum[it];
+            for (int it = 0; it < IT; it++) {
+                va[it] = *(const float4*)(src[it] + base);
+                vb[it] = *(const float4*)(src[it] + base + 16);
+            }
+#pragma unroll
+            for (int it = 0; it < IT; it++) {
+                sa[it].x += va[it].x; sa[it].y += va[it].y; sa[it].z += va[it].z; sa[it].w += va[it].w;
+                sb[it].x += vb[it].x; sb[it].y += vb[it].y; sb[it].z += vb[it].z; sb[it].w += vb[it].w;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT; it++) {
+            const int idx = it * 256 + threadIdx.x;
+            if ((idx >> 5) >= rows) continue;
+            const int row = row_lo + (idx >> 5), cb = (idx >> 2) & 7, fq = idx & 3;
+            const float av[4] = {sa[it].x, sa[it].y, sa[it].z, sa[it].w};
+            const float bv[4] = {sb[it].x, sb[it].y, sb[it].z, sb[it].w};
+            float hv[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) hv[q] = av[q] / (1.0f + __expf(-av[q])) * bv[q];
+            // same fragment address as the first projection's own epilogue
+            const int blk = ti.blk0 + (row >> 4), t = row & 15;
+            const int colblk = ti.nt * (GG_FROWS / 2) + cb;
+            const int ks_o = colblk >> 1;
+            const int lane_o = ((colblk & 1) * 2 + (fq >> 1)) * 16 + t;
+            uint2 pk;
+            pk.x = moe_pack_bf16x2(hv[0], hv[1]);
+            pk.y = moe_pack_bf16x2(hv[2], hv[3]);
+            *(uint2*)((unsigned char*)a.out +
+                      (((size_t)(ti.si.bbase + blk) * a.KS_out + ks_o) * 64 + lane_o) * 16 +
+                      (fq & 1) * 8) = pk;
+        }
+    } else {
+        constexpr int IT = GG_FIX_ROWS * 64 / 256;  // float4 per thread
+        float4 sum[IT];
+        const float* src[IT];
+#pragma unroll
+        for (int it = 0; it < IT; it++) {
+            const int idx = it * 256 + threadIdx.x;
+            // rows past the end of the tile read row 0 of the group instead (never stored)
+            const int row = row_lo + ((idx >> 6) < rows ? (idx >> 6) : 0);
+            src[it] = a.part + (size_t)row * 256 + (idx & 63) * 4;
+            sum[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        for (int p = 0; p < n; p++) {
+            const size_t base = (size_t)s_slot[p] * 256 * 256;
+            float4 v[IT];
+#pragma unroll
+            for (int it = 0; it < IT; it++) v[it] = *(const float4*)(src[it] + base);
+#pragma unroll
+            for (int it = 0; it < IT; it++) {
+                sum[it].x += v[it].x; sum[it].y += v[it].y; sum[it].z += v[it].z; sum[it].w += v[it].w;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT; it++) {
+            const int idx = it * 256 + threadIdx.x;
+            if ((idx >> 6) < rows)
+                *(float4*)((float*)a.out +
+                           (size_t)(ti.si.row0 + ti.blk0 * 16 + row_lo + (idx >> 6)) * a.C +
+                           ti.nt * GG_FROWS * 16 + (idx & 63) * 4) = sum[it];
+        }
     }
 }
 
@@ -650,17 +728,21 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     const size_t lds_bytes = GG_NS * 16 * MOE_FRAG_BYTES;
     const unsigned pgrid = (unsigned)((moe_num_cus() + 7) / 8 * 8);  // persistent: one per CU
 
-    const void* k_up = up8 ? (const void*)gg_gemm_kernel<true, 8, 5, true>
-                           : (const void*)gg_gemm_kernel<true, 4, 3, false>;
-    const void* k_dn = dn8 ? (const void*)gg_gemm_kernel<false, 8, 5, true>
-                           : (const void*)gg_gemm_kernel<false, 4, 3, false>;
+    const void* k_up = up8 ? (const void*)gg_gemm_kernel<true, 8, 5, true, 1>
+                           : (const void*)gg_gemm_kernel<true, 4, 3, false, 1>;
+    const void* k_up_pieces = up8 ? (const void*)gg_gemm_kernel<true, 8, 5, true, 2>
+                                  : (const void*)gg_gemm_kernel<true, 4, 3, false, 2>;
+    const void* k_dn = dn8 ? (const void*)gg_gemm_kernel<false, 8, 5, true, 0>
+                           : (const void*)gg_gemm_kernel<false, 4, 3, false, 0>;
     static bool attr_set = false;
     if (!attr_set) {
-        const void* all[4] = {(const void*)gg_gemm_kernel<true, 8, 5, true>,
-                              (const void*)gg_gemm_kernel<true, 4, 3, false>,
-                              (const void*)gg_gemm_kernel<false, 8, 5, true>,
-                              (const void*)gg_gemm_kernel<false, 4, 3, false>};
-        for (int i = 0; i < 4; i++)
+        const void* all[6] = {(const void*)gg_gemm_kernel<true, 8, 5, true, 1>,
+                              (const void*)gg_gemm_kernel<true, 4, 3, false, 1>,
+                              (const void*)gg_gemm_kernel<true, 8, 5, true, 2>,
+                              (const void*)gg_gemm_kernel<true, 4, 3, false, 2>,
+                              (const void*)gg_gemm_kernel<false, 8, 5, true, 0>,
+                              (const void*)gg_gemm_kernel<false, 4, 3, false, 0>};
+        for (int i = 0; i < 6; i++)
             MOE_HIP_TRY(hipFuncSetAttribute(all[i], hipFuncAttributeMaxDynamicSharedMemorySize,
                                             (int)lds_bytes));
         attr_set = true;
@@ -684,12 +766,24 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.NT = up.FR / GG_FROWS;
     up.KS_out = f / 32;
     up.C = 0;
-    up.split = 0;
-    up.part = nullptr;
+    // Left-over tiles of each XCD (tile count not a multiple of the workgroup count) are cut
+    // along the reduction; pieces of >= 32 steps go to scratch behind hp and a fix-up kernel
+    // adds them (and applies SiLU*mul for the first projection).
+    float* part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
+                           gg_align256(nb * 16 * f * 2));
+    up.split = (d / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;  // the fix-up lists pieces with one wave
+    up.part = part;
     {
         void* params[1] = {(void*)&up};
         MOE_HIP_TRY(hipLaunchKernel(k_up, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
     }
+    if (up.split) {
+        void* params[1] = {(void*)&up};
+        MOE_HIP_TRY(hipLaunchKernel(k_up_pieces, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
+    }
+    if (up.split)
+        hipLaunchKernelGGL(gg_fixup_kernel<true>, dim3(pgrid, 256 / GG_FIX_ROWS), dim3(256), 0, s, up,
+                           (int)(pgrid / 8), up8 ? 8 : 4);
     moe_record_mid_event(s);
 
     GroupedArgs dn;
@@ -703,17 +797,14 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.NT = dn.FR / GG_FROWS;
     dn.KS_out = 0;
     dn.C = d;
-    // Cutting left-over tiles along the reduction needs pieces of >= 32 steps; the pieces
-    // are stored in scratch behind hp and summed by gg_fixup_kernel.
-    dn.split = (f / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;  // the fix-up lists pieces with one wave
-    dn.part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
-                       gg_align256(nb * 16 * f * 2));
+    dn.split = (f / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;
+    dn.part = part;
     {
         void* params[1] = {(void*)&dn};
         MOE_HIP_TRY(hipLaunchKernel(k_dn, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
     }
     if (dn.split)
-        hipLaunchKernelGGL(gg_fixup_kernel, dim3(pgrid, 256 / GG_FIX_ROWS), dim3(256), 0, s, dn,
+        hipLaunchKernelGGL(gg_fixup_kernel<false>, dim3(pgrid, 256 / GG_FIX_ROWS), dim3(256), 0, s, dn,
                            (int)(pgrid / 8), dn8 ? 8 : 4);
     return moe_launch_status();
 }

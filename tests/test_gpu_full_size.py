@@ -95,12 +95,17 @@ def test_prefill_layer_sampled_rows(moe, shape_weights, name):
     ref = dict(idx=idx, w=w, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm)
     _check_index_outputs(out, ref)
     print("prefill counts", counts.tolist())
-    # sampled rows of yg: first, last, two inner rows of each expert segment
+    # sampled rows of yg: first, last, two inner rows of each expert segment, plus rows of
+    # several 16-row blocks of its first and last tile
     rows = []
     for e in range(cfg.E):
         lo, hi = int(offsets[e]), int(offsets[e + 1])
         if hi > lo:
-            rows += sorted({lo, hi - 1, lo + (hi - lo) // 3, lo + (2 * (hi - lo)) // 3})
+            cand = {lo, hi - 1, lo + (hi - lo) // 3, lo + (2 * (hi - lo)) // 3}
+            # and rows in other 16-row blocks of the first and the last 256-row tile
+            last_tile = lo + ((hi - lo - 1) // 256) * 256
+            cand |= {base + 16 * b + 5 for base in (lo, last_tile) for b in (1, 6, 11, 15)}
+            rows += sorted(r for r in cand if lo <= r < hi)
     rows = np.array(rows)
     x64 = mi.to_f64(x)
     xg_s = x64[perm[rows] // cfg.k]
