@@ -41,10 +41,13 @@
 //     order per XCD.
 #include "moe_internal.h"
 
-#define GG_TILE_BLOCKS 16  // 16-row blocks per token tile (256 rows)
-#define GG_FROWS 16        // weight fragment rows per workgroup tile (256 features)
+// Tile shapes (token blocks of 16 rows x weight fragment rows of 16 features per workgroup;
+// a wave owns all token blocks x FRW = fragment rows / 4; 64 MFMA tiles per wave either way):
+//   16 x 16 (256 tokens x 256 features): the default;
+//    8 x 32 (128 tokens x 512 features): experts with up to ~128 rows, where the default
+//           tile is half empty -- twice the weight bytes per step, no padded matrix work.
 #define GG_THREADS 256
-#define GG_NS 8            // LDS stages of 16 B fragments (16 KiB each)
+#define GG_NS 8            // LDS stages of B fragments (one KiB per token block each)
 // The weight fragments of step k are requested LA steps earlier into a register ring that
 // is named statically, so the step loop is unrolled U times (LA < U, reduction % U == 0).
 // Two variants: U = 4, LA = 3 (the default) and U = 8, LA = 5 with the matrix instructions
@@ -52,10 +55,12 @@
 // the weight stream from HBM and gain from more bytes in flight (5 is what the 8 LDS
 // stages allow, see the waits in the step).
 #define GG_U_MIN 4
+#ifndef GG_WIDE_MAX_ROWS
+#define GG_WIDE_MAX_ROWS 96  // mean rows per expert up to which the 128 x 512 tile is used
+#endif
 #ifndef GG_RAGGED_VARIANT
 #define GG_RAGGED_VARIANT 1
 #endif
-#define GG_VMEM_PER_STEP 8 // vector-memory requests per wave and step (4 B + 4 A)
 
 // ---- segment bookkeeping: expert e owns blocks [bbase_e, bbase_e + ceil(M_e/16)) ----
 struct SegInfo {
@@ -129,11 +134,13 @@ struct GroupedArgs {
     int E, N;
     int KS;      // reduction steps of 32
     int FR;      // weight fragment rows per expert (up: 2*f/16, down: d/16)
-    int NT;      // workgroup tiles along the features = FR / GG_FROWS
+    int TB;      // token blocks (of 16 rows) per tile: 16 or 8
+    int FROWS;   // weight fragment rows per tile: 16 or 32
+    int NT;      // workgroup tiles along the features = FR / FROWS
     int KS_out;  // up: f/32 (fragment columns of hp); down: unused
     int C;       // down: d (row length of yg)
     int split;   // deal the left-over tiles of each XCD in pieces of their reduction
-    float* part; // split: partial tiles [8 XCDs][workgroups per XCD][2][256][256] fp32
+    float* part; // split: partial tiles [8 XCDs][workgroups per XCD][2][16*TB][16*FROWS] fp32
 };
 
 // s_waitcnt with only one counter constrained (gfx9 encoding: vmcnt = bits 3:0 and
@@ -146,22 +153,22 @@ struct TileInfo {
     int tis;   // token tile inside the segment
     int nt;    // feature tile
     int blk0;  // first block of the tile inside the segment
-    int nblk;  // blocks of the tile that exist (1..16)
+    int nblk;  // blocks of the tile that exist (1..TB)
     // the part of the tile's reduction this unit of work covers (whole tile: 0, KS)
     int k_lo, klen;
     bool partial;
     int piece;  // 0 or 1: which of this workgroup's two partial-tile slots it writes
 };
 
-// Number of logical tiles = NT * sum_e ceil(M_e / 256).
+// Number of logical tiles = NT * sum_e ceil(M_e / (16 * TB)).
 __device__ __forceinline__ int gg_total_tiles(const int32_t* __restrict__ offsets, int E, int N,
-                                              int NT) {
+                                              int NT, int TB) {
     int total = 0, prev = 0;
     for (int e = 0; e < E; e++) {
         const int lo = gg_clamp_off(offsets[e], prev, N);
         const int hi = gg_clamp_off(offsets[e + 1], lo, N);
         prev = lo;
-        total += ((hi - lo + 16 * GG_TILE_BLOCKS - 1) / (16 * GG_TILE_BLOCKS)) * NT;
+        total += ((hi - lo + 16 * TB - 1) / (16 * TB)) * NT;
     }
     return total;
 }
@@ -169,21 +176,21 @@ __device__ __forceinline__ int gg_total_tiles(const int32_t* __restrict__ offset
 // Logical tile index -> tile.  Logical order: expert, then feature tile, then token
 // tile (fastest), so that neighbouring indices share the same weight tile.
 __device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offsets, int E, int N,
-                                               int NT, int L, TileInfo& ti) {
+                                               int NT, int TB, int L, TileInfo& ti) {
     int base = 0, bb = 0, prev = 0;
     for (int e = 0; e < E; e++) {
         const int lo = gg_clamp_off(offsets[e], prev, N);
         const int hi = gg_clamp_off(offsets[e + 1], lo, N);
         prev = lo;
         const int nb = (hi - lo + 15) / 16;
-        const int tiles = (nb + GG_TILE_BLOCKS - 1) / GG_TILE_BLOCKS;
+        const int tiles = (nb + TB - 1) / TB;
         if (L < base + tiles * NT) {
             const int r = L - base;
             ti.nt = r / tiles;
             ti.tis = r % tiles;
             ti.si.e = e; ti.si.row0 = lo; ti.si.rows = hi - lo; ti.si.bbase = bb;
-            ti.blk0 = ti.tis * GG_TILE_BLOCKS;
-            ti.nblk = (nb - ti.blk0) < GG_TILE_BLOCKS ? (nb - ti.blk0) : GG_TILE_BLOCKS;
+            ti.blk0 = ti.tis * TB;
+            ti.nblk = (nb - ti.blk0) < TB ? (nb - ti.blk0) : TB;
             ti.k_lo = 0;
             ti.klen = 0;  // filled in by the caller
             ti.partial = false;
@@ -255,21 +262,23 @@ __device__ __forceinline__ void gg_mfma_quad(f32x4_t (&c0)[4], f32x4_t (&c1)[4],
 }
 
 // Global source pointers of one tile for this wave (all wave-uniform).
+template <int FRW, int NBQ>
 struct TileSrc {
-    const u32x4_t* a[4];  // this wave's 4 weight fragment rows (start of the reduction)
-    const u32x4_t* b[4];  // the 4 token blocks this wave requests into LDS
+    const u32x4_t* a[FRW];  // this wave's weight fragment rows (start of the reduction)
+    const u32x4_t* b[NBQ];  // the token blocks this wave requests into LDS
 };
 
+template <int FRW, int NBQ>
 __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo& ti, int wave,
-                                            TileSrc& ts) {
+                                            TileSrc<FRW, NBQ>& ts) {
 #pragma unroll
-    for (int j = 0; j < 4; j++)
+    for (int j = 0; j < FRW; j++)
         ts.a[j] = a.wfrag +
-                  (((size_t)ti.si.e * a.FR + (size_t)ti.nt * GG_FROWS + 4 * wave + j) * a.KS + ti.k_lo) * 64;
+                  (((size_t)ti.si.e * a.FR + (size_t)ti.nt * (4 * FRW) + FRW * wave + j) * a.KS + ti.k_lo) * 64;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        int blk = 4 * wave + i;
-        blk = blk < ti.nblk ? blk : ti.nblk - 1;  // clamp: every wave always issues 4 requests
+    for (int i = 0; i < NBQ; i++) {
+        int blk = NBQ * wave + i;
+        blk = blk < ti.nblk ? blk : ti.nblk - 1;  // clamp: every wave always issues NBQ requests
         ts.b[i] = a.bfrag + (((size_t)(ti.si.bbase + ti.blk0 + blk)) * a.KS + ti.k_lo) * 64;
     }
 }
@@ -278,13 +287,19 @@ __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo
 // one epilogue serves both), 1 = whole tiles only, 2 = pieces only (the first projection
 // takes two launches, because an epilogue with both the SiLU*mul body and the raw store of
 // partial sums makes the compiler spill ~150 accumulators per tile).
-template <bool UP, int U, int LA, bool SKIP, int MODE>  // LA < U, LA <= GG_NS - 3
+// NBW x FRW: token blocks of the tile x fragment rows of a wave (16 x 4 or 8 x 8).
+template <bool UP, int NBW, int FRW, int U, int LA, bool SKIP, int MODE>  // LA < U, LA <= GG_NS - 3
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
+    static_assert(NBW * FRW == 64 && NBW % 4 == 0, "64 MFMA tiles per wave");
+    static_assert(!SKIP || (NBW == 16 && FRW == 4), "quarter skipping is written for 16 x 4");
+    constexpr int FROWS = 4 * FRW;     // fragment rows of the workgroup tile
+    constexpr int NBQ = NBW / 4;       // token blocks each wave requests into LDS per step
+    constexpr int VREQ = FRW + NBQ;    // vector-memory requests per wave and step
     extern __shared__ __align__(16) unsigned char smem[];
-    u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][16 fragments][64 lanes]
+    u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][NBW fragments][64 lanes]
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // fragment rows [4*wave, +4)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // fragment rows [FRW*wave, +FRW)
     const unsigned voff = (unsigned)lane * 16u;                  // byte offset inside a fragment
 
     // This workgroup's units of work.  The logical tiles of XCD x are x*per_xcd ... ; the
@@ -294,7 +309,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     // left-over tiles are cut along the reduction instead, in equal pieces for all
     // workgroups; every piece stores its partial sums into scratch and gg_fixup_kernel adds
     // the pieces of a tile in a fixed order (then applies SiLU*mul, first projection).
-    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
+    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT, NBW);
     const int per_xcd = (total + 7) / 8;
     const int xcd = blockIdx.x & 7;
     const int wgs = gridDim.x >> 3;
@@ -331,7 +346,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             lo = pc_lo[n - n_full];
             len = pc_len[n - n_full];
         }
-        if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + sl, ti)) return false;
+        if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, NBW, xcd * per_xcd + sl, ti)) return false;
         ti.k_lo = lo;
         ti.klen = len;
         ti.partial = (n >= n_full);  // pieces always go through scratch and the fix-up
@@ -343,7 +358,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     TileInfo cur, nxt;
     if (!unit_at(unit, cur)) return;
     bool has_next = unit_at(unit + 1, nxt);
-    TileSrc scur, snxt;
+    TileSrc<FRW, NBQ> scur, snxt;
     gg_tile_src(a, cur, wave, scur);
     if (has_next) gg_tile_src(a, nxt, wave, snxt); else snxt = scur;
     int KT = cur.klen;  // steps of the current unit: a multiple of 4, >= GG_NS
@@ -361,34 +376,34 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     auto issue_b = [&](int i, int j, int gstage) {
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void*)b_src(i, j),
-            (__attribute__((address_space(3))) void*)(lds + ((gstage % GG_NS) * 16 + 4 * wave + i) * 64),
+            (__attribute__((address_space(3))) void*)(lds + ((gstage % GG_NS) * NBW + NBQ * wave + i) * 64),
             16, 0, 0);
     };
 
-    f32x4_t acc[16][4];
-    u32x4_t areg[U][4];
-    bf16x8_t breg[16];
+    f32x4_t acc[NBW][FRW];
+    u32x4_t areg[U][FRW];
+    bf16x8_t breg[NBW];
 
     // ---- prologue of the first tile: request stages 0..NS-2 and A of steps 0..PA-2 ----
     for (int j = 0; j < GG_NS - 1; j++)
 #pragma unroll
-        for (int i = 0; i < 4; i++) issue_b(i, j, j);
+        for (int i = 0; i < NBQ; i++) issue_b(i, j, j);
 #pragma unroll
     for (int s = 0; s < LA; s++)
 #pragma unroll
-        for (int j = 0; j < 4; j++) areg[s][j] = *a_src(j, s);
+        for (int j = 0; j < FRW; j++) areg[s][j] = *a_src(j, s);
     GG_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int i = 0; i < 16; i++) breg[i] = __builtin_bit_cast(bf16x8_t, lds[i * 64 + lane]);
+    for (int i = 0; i < NBW; i++) breg[i] = __builtin_bit_cast(bf16x8_t, lds[i * 64 + lane]);
     GG_WAIT_LGKM(0);
 
     int g = 0;  // running step count
     for (;;) {
 #pragma unroll
-        for (int i = 0; i < 16; i++)
+        for (int i = 0; i < NBW; i++)
 #pragma unroll
-            for (int j = 0; j < 4; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int j = 0; j < FRW; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         // the compiler cannot see the MFMAs below: cover the register write -> matrix read hazard
         asm volatile("s_nop 7" ::: "memory");
 
@@ -397,7 +412,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         // the current tile, so there is nothing to decide (compile-time after inlining).
         // quarters of the tile's rows that hold tokens (SKIP: the others do no arithmetic)
         const int nquads = __builtin_amdgcn_readfirstlane((cur.nblk + 3) >> 2);
-        auto step = [&](int k, u32x4_t(&Ac)[4], u32x4_t(&An)[4], const bool fast) {
+        auto step = [&](int k, u32x4_t(&Ac)[FRW], u32x4_t(&An)[FRW], const bool fast) {
             // do the look-ahead requests exist (in this tile or the next one)?
             const bool la_b = fast || has_next || (k + GG_NS - 1 < KT);
             const bool la_a = fast || has_next || (k + LA < KT);
@@ -407,49 +422,50 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             // LA-1 steps' worth still in flight they have arrived, and so have the stages
             // requested before them (LA <= GG_NS-3: up to stage k+2).  Once the stream has
             // ended (last tile, no look-ahead) wait for everything.
-            if (la_b) GG_WAIT_VMCNT((LA - 1) * GG_VMEM_PER_STEP);
+            if (la_b) GG_WAIT_VMCNT((LA - 1) * VREQ);
             else GG_WAIT_VMCNT(0);
             // One barrier per TWO steps: at an even step every wave has waited for its
             // shares of stages k+1 and k+2 (see above), so both are published here; and the
             // buffers refilled during steps k and k+1 (stages k-1 and k) were last read
             // before this barrier.
             if (more && (k & 1) == 0) __builtin_amdgcn_s_barrier();
-            const u32x4_t* pb = lds + ((g + 1) % GG_NS) * 16 * 64 + lane;
-            // request number v of this step: 0..3 = this wave's 4 blocks of stage k+GG_NS-1
-            // (straight into LDS), 4..7 = its 4 weight fragments of step k+LA
+            const u32x4_t* pb = lds + ((g + 1) % GG_NS) * NBW * 64 + lane;
+            // request number v of this step: 0..NBQ-1 = this wave's blocks of stage k+GG_NS-1
+            // (straight into LDS), NBQ.. = its FRW weight fragments of step k+LA
             auto issue = [&](const int v) {
-                    if (v < 4) {
+                    if (v < NBQ) {
                         if (fast) {
                             __builtin_amdgcn_global_load_lds(
                                 (const __attribute__((address_space(1))) void*)(
                                     (const char*)(scur.b[v] + (size_t)(k + GG_NS - 1) * 64) + voff),
                                 (__attribute__((address_space(3))) void*)(
-                                    lds + (((g + GG_NS - 1) % GG_NS) * 16 + 4 * wave + v) * 64),
+                                    lds + (((g + GG_NS - 1) % GG_NS) * NBW + NBQ * wave + v) * 64),
                                 16, 0, 0);
                         } else if (la_b) {
                             issue_b(v, k + GG_NS - 1, g + GG_NS - 1);
                         }
                     } else {
                         if (fast)
-                            An[v - 4] = *(const u32x4_t*)((const char*)(scur.a[v - 4] +
-                                                          (size_t)(k + LA) * 64) + voff);
+                            An[v - NBQ] = *(const u32x4_t*)((const char*)(scur.a[v - NBQ] +
+                                                            (size_t)(k + LA) * 64) + voff);
                         else if (la_a)
-                            An[v - 4] = *a_src(v - 4, k + LA);
+                            An[v - NBQ] = *a_src(v - NBQ, k + LA);
                     }
             };
             if constexpr (!SKIP) {
 #pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    // one vector-memory request per 8 MFMAs, so that the requests of the four
-                    // waves never queue up in front of the matrix instructions
-                    if ((i & 1) == 0) {
-                        issue(i >> 1);
-                        // LDS reads return in order: with at most 14 younger ones in flight,
-                        // breg[i] and breg[i+1] (refilled one step ago) have arrived
-                        GG_WAIT_LGKM(14);
-                    }
+                for (int i = 0; i < NBW; i++) {
+                    // the vector-memory requests are spread evenly over the blocks (one per
+                    // 8 MFMAs for 16 x 4), so that the requests of the four waves never
+                    // queue up in front of the matrix instructions
 #pragma unroll
-                    for (int j = 0; j < 4; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
+                    for (int v = (i * VREQ + NBW - 1) / NBW; v < ((i + 1) * VREQ + NBW - 1) / NBW; v++)
+                        issue(v);
+                    // LDS reads return in order: with at most NBW-2 younger ones in flight,
+                    // breg[i] and breg[i+1] (refilled one step ago) have arrived
+                    if ((i & 1) == 0) GG_WAIT_LGKM(NBW - 2);
+#pragma unroll
+                    for (int j = 0; j < FRW; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
                     if (more) breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
                 }
             } else {
@@ -487,32 +503,33 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         // the compiler cannot see the MFMAs: cover the matrix-core write -> read hazard
         asm volatile("s_nop 15\n s_nop 15" ::: "memory");
         const int t = lane & 15, fq = lane >> 4;  // token in block, feature quad
+        // a piece's partial sums: [16*NBW rows][16*FROWS columns] fp32 in this workgroup's slot
+        float* slot = a.part + (((size_t)xcd * wgs + me) * 2 + cur.piece) * (256 * 256) +
+                      (size_t)t * (16 * FROWS) + (FRW * wave) * 16 + 4 * fq;
         if (UP && MODE == 2) {
-            // piece of a tile: raw partial sums to this workgroup's scratch slot; the fix-up
-            // kernel adds the pieces and applies SiLU*mul
-            float* slot = a.part + ((((size_t)xcd * wgs + me) * 2 + cur.piece) * 256 + t) * 256 +
-                          (4 * wave) * 16 + 4 * fq;
+            // piece of a tile: raw partial sums to scratch; the fix-up kernel adds the
+            // pieces and applies SiLU*mul
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
+            for (int i = 0; i < NBW; i++) {
                 if (i >= cur.nblk) continue;
 #pragma unroll
-                for (int j = 0; j < 4; j++)
-                    *(float4*)(slot + (size_t)i * 16 * 256 + j * 16) =
+                for (int j = 0; j < FRW; j++)
+                    *(float4*)(slot + (size_t)i * 16 * (16 * FROWS) + j * 16) =
                         make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
             }
         } else if (UP) {
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
+            for (int i = 0; i < NBW; i++) {
                 if (i >= cur.nblk) continue;
                 const int blk = cur.blk0 + i;  // block inside the segment
-                // fragment rows 4*wave+j: j even = w1 rows, j odd = w3 rows of the same columns
+                // fragment rows FRW*wave+j: j even = w1 rows, j odd = w3 rows of the same columns
 #pragma unroll
-                for (int jj = 0; jj < 2; jj++) {
+                for (int jj = 0; jj < FRW / 2; jj++) {
                     const f32x4_t av = acc[i][2 * jj], bv = acc[i][2 * jj + 1];
                     float hv[4];
 #pragma unroll
                     for (int r = 0; r < 4; r++) hv[r] = av[r] / (1.0f + __expf(-av[r])) * bv[r];
-                    const int colblk = cur.nt * (GG_FROWS / 2) + 2 * wave + jj;  // 16 h-columns
+                    const int colblk = cur.nt * (FROWS / 2) + (FRW / 2) * wave + jj;  // 16 h-columns
                     const int ks_o = colblk >> 1;
                     const int lane_o = ((colblk & 1) * 2 + (fq >> 1)) * 16 + t;
                     uint2 pk;
@@ -527,21 +544,18 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
+            for (int i = 0; i < NBW; i++) {
                 if (i >= cur.nblk) continue;
                 const int blk = cur.blk0 + i;  // block inside the segment
                 // whole tiles go to yg; pieces of a tile to this workgroup's scratch slot
                 // (same code, only the destination differs)
                 const int r_in_seg = blk * 16 + t;
                 if (r_in_seg < cur.si.rows) {
-                    float* row =
-                        cur.partial
-                            ? a.part + ((((size_t)xcd * wgs + me) * 2 + cur.piece) * 256 + i * 16 + t) * 256 +
-                                  (4 * wave) * 16 + 4 * fq
-                            : (float*)a.out + (size_t)(cur.si.row0 + r_in_seg) * a.C +
-                                  (cur.nt * GG_FROWS + 4 * wave) * 16 + 4 * fq;
+                    float* row = cur.partial ? slot + (size_t)i * 16 * (16 * FROWS)
+                                             : (float*)a.out + (size_t)(cur.si.row0 + r_in_seg) * a.C +
+                                                   (cur.nt * FROWS + FRW * wave) * 16 + 4 * fq;
 #pragma unroll
-                    for (int j = 0; j < 4; j++)
+                    for (int j = 0; j < FRW; j++)
                         *(float4*)(row + j * 16) =
                             make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
                 }
@@ -559,17 +573,19 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     }
 }
 
-// Adds the pieces of every left-over tile of the second projection into yg, in the order
-// of the workgroups that produced them (deterministic).  blockIdx.x = (XCD, left-over
-// tile), blockIdx.y = group of 16 rows of the tile; every workgroup recomputes the cut
-// points the GEMM workgroups used.
+// Adds the pieces of every left-over tile in the order of the workgroups that produced them
+// (deterministic), then writes yg (second projection) or applies SiLU*mul and writes the h
+// fragments (first projection).  blockIdx.x = (XCD, left-over tile), blockIdx.y = group of
+// 16 rows of the tile; every workgroup recomputes the cut points the GEMM workgroups used.
+// FROWS = fragment rows of the tile shape (16 or 32); a.TB = its token blocks.
 #define GG_FIX_ROWS 16
-template <bool UP>
+template <bool UP, int FROWS>
 __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, int unit) {
     __shared__ int s_slot[64];
     __shared__ int s_n;
+    constexpr int RS = 16 * FROWS;  // floats per row of a partial tile
     const int xcd = blockIdx.x / wgs, r = blockIdx.x % wgs;
-    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT);
+    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT, a.TB);
     const int per_xcd = (total + 7) / 8;
     int chunk = total - xcd * per_xcd;
     chunk = chunk < 0 ? 0 : (chunk > per_xcd ? per_xcd : chunk);
@@ -578,11 +594,13 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
     const int R = chunk - n_full * wgs;
     if (r >= R) return;
     TileInfo ti;
-    if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, xcd * per_xcd + n_full * wgs + r, ti)) return;
+    if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, a.TB, xcd * per_xcd + n_full * wgs + r, ti)) return;
     // second projection: the tile's real rows; first: every row of its blocks (h is kept in
     // whole 16-row fragments, padding rows included)
+    const int tile_max = 16 * a.TB;
     const int tile_rows = UP ? ti.nblk * 16
-                             : ((ti.si.rows - ti.blk0 * 16) < 256 ? (ti.si.rows - ti.blk0 * 16) : 256);
+                             : ((ti.si.rows - ti.blk0 * 16) < tile_max ? (ti.si.rows - ti.blk0 * 16)
+                                                                       : tile_max);
     const int row_lo = blockIdx.y * GG_FIX_ROWS;
     if (row_lo >= tile_rows) return;
     // lane j of the first wave looks at workgroup j's cut: it holds at most one piece of
@@ -611,14 +629,16 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
     if (UP) {
         // item = (row, block of 16 h-columns cb, feature quad fq): a = x.w1 from fragment
         // row 2cb, b = x.w3 from fragment row 2cb+1, four columns each
-        constexpr int IT = GG_FIX_ROWS * 32 / 256;
+        constexpr int PER_ROW = (FROWS / 2) * 4;
+        constexpr int IT = GG_FIX_ROWS * PER_ROW / 256;
         float4 sa[IT], sb[IT];
         const float* src[IT];
 #pragma unroll
         for (int it = 0; it < IT; it++) {
             const int idx = it * 256 + threadIdx.x;
-            const int rr = (idx >> 5) < rows ? (idx >> 5) : 0, cb = (idx >> 2) & 7, fq = idx & 3;
-            src[it] = a.part + (size_t)(row_lo + rr) * 256 + (2 * cb) * 16 + 4 * fq;
+            const int rr = (idx / PER_ROW) < rows ? (idx / PER_ROW) : 0;
+            const int cb = (idx >> 2) % (FROWS / 2), fq = idx & 3;
+            src[it] = a.part + (size_t)(row_lo + rr) * RS + (2 * cb) * 16 + 4 * fq;
             sa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
             sb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
@@ -639,8 +659,8 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
 #pragma unroll
         for (int it = 0; it < IT; it++) {
             const int idx = it * 256 + threadIdx.x;
-            if ((idx >> 5) >= rows) continue;
-            const int row = row_lo + (idx >> 5), cb = (idx >> 2) & 7, fq = idx & 3;
+            if ((idx / PER_ROW) >= rows) continue;
+            const int row = row_lo + idx / PER_ROW, cb = (idx >> 2) % (FROWS / 2), fq = idx & 3;
             const float av[4] = {sa[it].x, sa[it].y, sa[it].z, sa[it].w};
             const float bv[4] = {sb[it].x, sb[it].y, sb[it].z, sb[it].w};
             float hv[4];
@@ -648,7 +668,7 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
             for (int q = 0; q < 4; q++) hv[q] = av[q] / (1.0f + __expf(-av[q])) * bv[q];
             // same fragment address as the first projection's own epilogue
             const int blk = ti.blk0 + (row >> 4), t = row & 15;
-            const int colblk = ti.nt * (GG_FROWS / 2) + cb;
+            const int colblk = ti.nt * (FROWS / 2) + cb;
             const int ks_o = colblk >> 1;
             const int lane_o = ((colblk & 1) * 2 + (fq >> 1)) * 16 + t;
             uint2 pk;
@@ -659,15 +679,16 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
                       (fq & 1) * 8) = pk;
         }
     } else {
-        constexpr int IT = GG_FIX_ROWS * 64 / 256;  // float4 per thread
+        constexpr int PER_ROW = RS / 4;                      // float4 per row
+        constexpr int IT = GG_FIX_ROWS * PER_ROW / 256;      // float4 per thread
         float4 sum[IT];
         const float* src[IT];
 #pragma unroll
         for (int it = 0; it < IT; it++) {
             const int idx = it * 256 + threadIdx.x;
             // rows past the end of the tile read row 0 of the group instead (never stored)
-            const int row = row_lo + ((idx >> 6) < rows ? (idx >> 6) : 0);
-            src[it] = a.part + (size_t)row * 256 + (idx & 63) * 4;
+            const int row = row_lo + ((idx / PER_ROW) < rows ? (idx / PER_ROW) : 0);
+            src[it] = a.part + (size_t)row * RS + (idx % PER_ROW) * 4;
             sum[it] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
         for (int p = 0; p < n; p++) {
@@ -683,10 +704,10 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
 #pragma unroll
         for (int it = 0; it < IT; it++) {
             const int idx = it * 256 + threadIdx.x;
-            if ((idx >> 6) < rows)
+            if ((idx / PER_ROW) < rows)
                 *(float4*)((float*)a.out +
-                           (size_t)(ti.si.row0 + ti.blk0 * 16 + row_lo + (idx >> 6)) * a.C +
-                           ti.nt * GG_FROWS * 16 + (idx & 63) * 4) = sum[it];
+                           (size_t)(ti.si.row0 + ti.blk0 * 16 + row_lo + idx / PER_ROW) * a.C +
+                           ti.nt * FROWS * 16 + (idx % PER_ROW) * 4) = sum[it];
         }
     }
 }
@@ -706,6 +727,18 @@ size_t moe_ffn_grouped_workspace(int N, int E, int d, int f) {
     return gg_align256(nb * 16 * d * 2) + gg_align256(nb * 16 * f * 2) + gg_part_bytes();
 }
 
+// Kernel variants by rows per expert (see the tile shapes at the top of the file).
+enum GgVariant { GG_STD = 0, GG_FEW = 1, GG_WIDE = 2 };
+
+template <bool UP, int MODE>
+static const void* gg_kernel_ptr(GgVariant v) {
+    switch (v) {
+        case GG_FEW: return (const void*)gg_gemm_kernel<UP, 16, 4, 8, 5, true, MODE>;
+        case GG_WIDE: return (const void*)gg_gemm_kernel<UP, 8, 8, 4, 3, false, MODE>;
+        default: return (const void*)gg_gemm_kernel<UP, 16, 4, 4, 3, false, MODE>;
+    }
+}
+
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
                            const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
     const int d = W->d, f = W->f, E = W->E;
@@ -716,35 +749,36 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     // the step loop is unrolled 4 or 8 times and looks GG_NS-1 steps ahead
     if ((d / 32) % GG_U_MIN != 0 || (f / 32) % GG_U_MIN != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
         return MOE_ERR_UNSUPPORTED;
-    // Few rows per expert (at most 40 on average, i.e. tiles with one quarter occupied):
-    // the variant with the deeper weight ring that skips empty row quarters.  Measured on
-    // the Mixtral shape it is 5-10 % faster up to 32 rows per expert and 2-3 % slower from
-    // 64 rows on.
-    const bool ragged = GG_RAGGED_VARIANT && (long long)N <= (long long)E * 40;
-    const bool up8 = ragged && (d / 32) % 8 == 0, dn8 = ragged && (f / 32) % 8 == 0;
+    // Variant by the mean number of rows per expert (the host never sees the real counts):
+    //   <= 40:  default tile, steps unrolled 8x, weights 5 steps ahead, empty row quarters
+    //           skipped (5-10 % faster than the default up to 32 rows, slower from 64 on);
+    //   <= GG_WIDE_MAX_ROWS: 128-token x 512-feature tile (needs f % 256 == 0 for the first
+    //           projection, d % 512 == 0 for the second; each falls back on its own);
+    //   else:   default.
+    const long long mean_rows = ((long long)N + E - 1) / E;
+    GgVariant vu = GG_STD, vd = GG_STD;
+    if (GG_RAGGED_VARIANT && mean_rows <= 40) {
+        if ((d / 32) % 8 == 0) vu = GG_FEW;
+        if ((f / 32) % 8 == 0) vd = GG_FEW;
+    } else if (mean_rows <= GG_WIDE_MAX_ROWS) {
+        if (f % 256 == 0) vu = GG_WIDE;
+        if (d % 512 == 0) vd = GG_WIDE;
+    }
     const size_t nb = gg_max_blocks(N, E);
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
-    const size_t lds_bytes = GG_NS * 16 * MOE_FRAG_BYTES;
+    const size_t lds_max = GG_NS * 16 * MOE_FRAG_BYTES;
     const unsigned pgrid = (unsigned)((moe_num_cus() + 7) / 8 * 8);  // persistent: one per CU
 
-    const void* k_up = up8 ? (const void*)gg_gemm_kernel<true, 8, 5, true, 1>
-                           : (const void*)gg_gemm_kernel<true, 4, 3, false, 1>;
-    const void* k_up_pieces = up8 ? (const void*)gg_gemm_kernel<true, 8, 5, true, 2>
-                                  : (const void*)gg_gemm_kernel<true, 4, 3, false, 2>;
-    const void* k_dn = dn8 ? (const void*)gg_gemm_kernel<false, 8, 5, true, 0>
-                           : (const void*)gg_gemm_kernel<false, 4, 3, false, 0>;
     static bool attr_set = false;
     if (!attr_set) {
-        const void* all[6] = {(const void*)gg_gemm_kernel<true, 8, 5, true, 1>,
-                              (const void*)gg_gemm_kernel<true, 4, 3, false, 1>,
-                              (const void*)gg_gemm_kernel<true, 8, 5, true, 2>,
-                              (const void*)gg_gemm_kernel<true, 4, 3, false, 2>,
-                              (const void*)gg_gemm_kernel<false, 8, 5, true, 0>,
-                              (const void*)gg_gemm_kernel<false, 4, 3, false, 0>};
-        for (int i = 0; i < 6; i++)
-            MOE_HIP_TRY(hipFuncSetAttribute(all[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)lds_bytes));
+        for (int v = 0; v < 3; v++) {
+            const void* all[3] = {gg_kernel_ptr<true, 1>((GgVariant)v), gg_kernel_ptr<true, 2>((GgVariant)v),
+                                  gg_kernel_ptr<false, 0>((GgVariant)v)};
+            for (int i = 0; i < 3; i++)
+                MOE_HIP_TRY(hipFuncSetAttribute(all[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                (int)lds_max));
+        }
         attr_set = true;
     }
 
@@ -755,6 +789,13 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
         hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets,
                            E, N, d, xp);
 
+    // Left-over tiles of each XCD (tile count not a multiple of the workgroup count) are cut
+    // along the reduction; pieces of >= 32 steps go to scratch behind hp and a fix-up kernel
+    // adds them (and applies SiLU*mul for the first projection).  The fix-up lists the
+    // pieces of a tile with one wave, hence at most 64 workgroups per XCD.
+    float* part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
+                           gg_align256(nb * 16 * f * 2));
+
     GroupedArgs up;
     up.wfrag = (const u32x4_t*)W->w13;
     up.bfrag = xp;
@@ -763,27 +804,31 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.E = E; up.N = N;
     up.KS = d / 32;
     up.FR = 2 * (f / 16);
-    up.NT = up.FR / GG_FROWS;
+    up.TB = vu == GG_WIDE ? 8 : 16;
+    up.FROWS = vu == GG_WIDE ? 32 : 16;
+    up.NT = up.FR / up.FROWS;
     up.KS_out = f / 32;
     up.C = 0;
-    // Left-over tiles of each XCD (tile count not a multiple of the workgroup count) are cut
-    // along the reduction; pieces of >= 32 steps go to scratch behind hp and a fix-up kernel
-    // adds them (and applies SiLU*mul for the first projection).
-    float* part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
-                           gg_align256(nb * 16 * f * 2));
-    up.split = (d / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;  // the fix-up lists pieces with one wave
+    up.split = (d / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;
     up.part = part;
     {
         void* params[1] = {(void*)&up};
-        MOE_HIP_TRY(hipLaunchKernel(k_up, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
+        const size_t lds_bytes = (size_t)GG_NS * up.TB * MOE_FRAG_BYTES;
+        const int unit = vu == GG_FEW ? 8 : 4;
+        MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 1>(vu), dim3(pgrid), dim3(GG_THREADS), params,
+                                    lds_bytes, s));
+        if (up.split) {
+            MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 2>(vu), dim3(pgrid), dim3(GG_THREADS),
+                                        params, lds_bytes, s));
+            const dim3 fgrid(pgrid, (unsigned)up.TB);
+            if (vu == GG_WIDE)
+                hipLaunchKernelGGL((gg_fixup_kernel<true, 32>), fgrid, dim3(256), 0, s, up,
+                                   (int)(pgrid / 8), unit);
+            else
+                hipLaunchKernelGGL((gg_fixup_kernel<true, 16>), fgrid, dim3(256), 0, s, up,
+                                   (int)(pgrid / 8), unit);
+        }
     }
-    if (up.split) {
-        void* params[1] = {(void*)&up};
-        MOE_HIP_TRY(hipLaunchKernel(k_up_pieces, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
-    }
-    if (up.split)
-        hipLaunchKernelGGL(gg_fixup_kernel<true>, dim3(pgrid, 256 / GG_FIX_ROWS), dim3(256), 0, s, up,
-                           (int)(pgrid / 8), up8 ? 8 : 4);
     moe_record_mid_event(s);
 
     GroupedArgs dn;
@@ -794,17 +839,28 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.E = E; dn.N = N;
     dn.KS = f / 32;
     dn.FR = d / 16;
-    dn.NT = dn.FR / GG_FROWS;
+    dn.TB = vd == GG_WIDE ? 8 : 16;
+    dn.FROWS = vd == GG_WIDE ? 32 : 16;
+    dn.NT = dn.FR / dn.FROWS;
     dn.KS_out = 0;
     dn.C = d;
     dn.split = (f / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;
     dn.part = part;
     {
         void* params[1] = {(void*)&dn};
-        MOE_HIP_TRY(hipLaunchKernel(k_dn, dim3(pgrid), dim3(GG_THREADS), params, lds_bytes, s));
+        const size_t lds_bytes = (size_t)GG_NS * dn.TB * MOE_FRAG_BYTES;
+        const int unit = vd == GG_FEW ? 8 : 4;
+        MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<false, 0>(vd), dim3(pgrid), dim3(GG_THREADS), params,
+                                    lds_bytes, s));
+        if (dn.split) {
+            const dim3 fgrid(pgrid, (unsigned)dn.TB);
+            if (vd == GG_WIDE)
+                hipLaunchKernelGGL((gg_fixup_kernel<false, 32>), fgrid, dim3(256), 0, s, dn,
+                                   (int)(pgrid / 8), unit);
+            else
+                hipLaunchKernelGGL((gg_fixup_kernel<false, 16>), fgrid, dim3(256), 0, s, dn,
+                                   (int)(pgrid / 8), unit);
+        }
     }
-    if (dn.split)
-        hipLaunchKernelGGL(gg_fixup_kernel<false>, dim3(pgrid, 256 / GG_FIX_ROWS), dim3(256), 0, s, dn,
-                           (int)(pgrid / 8), dn8 ? 8 : 4);
     return moe_launch_status();
 }

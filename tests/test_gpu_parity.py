@@ -163,7 +163,12 @@ def test_layer_bf16_stream_path(moe, T, d, f, E, k, xdt):
     (300, 512, 1024, 8, 2, mi.F32), (1100, 256, 256, 3, 1, mi.BF16),
     # few rows per expert: the deep-ring variant that skips empty row quarters; f = 384 keeps
     # the second projection on the default variant, f = 2304 cuts its tiles along the reduction
-    (70, 256, 384, 8, 2, mi.F32), (150, 512, 2304, 8, 2, mi.BF16), (9, 256, 2048, 16, 2, mi.BF16)])
+    (70, 256, 384, 8, 2, mi.F32), (150, 512, 2304, 8, 2, mi.BF16), (9, 256, 2048, 16, 2, mi.BF16),
+    # 41..96 rows per expert: the 128-token x 512-feature tile (first projection needs
+    # f % 256 == 0, second d % 512 == 0, else that projection keeps the default tile);
+    # d = 2048 / f = 2304 also cut left-over tiles along the reduction
+    (380, 1024, 2304, 8, 2, mi.BF16), (300, 256, 512, 8, 2, mi.F32), (330, 512, 384, 4, 1, mi.BF16),
+    (370, 2048, 512, 8, 2, mi.BF16)])
 def test_layer_bf16_grouped_path(moe, T, d, f, E, k, xdt):
     cfg = mi.small_config("gg", T, d, f, E, k, 600 + T + d, w_dtype=mi.BF16, x_dtype=xdt,
                           zipf_s=1.2)
