@@ -328,7 +328,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=None,
                     help="override T of a single-layer workload (sweeps; the JSON names it)")
-    ap.add_argument("--ffn-path", default="auto", choices=["auto", "stream", "grouped"],
+    ap.add_argument("--ffn-path", default="auto", choices=["auto", "stream", "grouped", "mid"],
                     help="force the expert-FFN kernel family (sweeps)")
     ap.add_argument("--fused-gate", action="store_true",
                     help="decode-sized workloads: use the one-launch moe_route_permute instead "
@@ -378,7 +378,7 @@ def main():
     xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
     step = Step(torch, moe, T, xs[0].dtype, fused_gate=args.fused_gate)
     step.ffn_path = {"auto": moe.MOE_FFN_AUTO, "stream": moe.MOE_FFN_STREAM,
-                     "grouped": moe.MOE_FFN_GROUPED}[args.ffn_path]
+                     "grouped": moe.MOE_FFN_GROUPED, "mid": moe.MOE_FFN_MID}[args.ffn_path]
     stream = torch.cuda.current_stream().cuda_stream
     events = HipEvents()
 

@@ -10,7 +10,7 @@ from typing import Optional
 import torch
 
 MOE_F32, MOE_BF16 = 0, 1
-MOE_FFN_AUTO, MOE_FFN_STREAM, MOE_FFN_GROUPED = 0, 1, 2
+MOE_FFN_AUTO, MOE_FFN_STREAM, MOE_FFN_GROUPED, MOE_FFN_MID = 0, 1, 2, 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libmoe_hip.so")

@@ -2,6 +2,11 @@
 // dispatch to the kernel launchers.  Nothing is enqueued when validation fails.
 #include "moe_internal.h"
 
+// mean rows per expert up to which AUTO takes the weight-streaming grouped GEMM
+#ifndef MOE_MID_MAX_ROWS
+#define MOE_MID_MAX_ROWS 40
+#endif
+
 static inline bool dims_ok(int d) { return d >= 64 && d % 64 == 0 && d <= (1 << 20); }
 static inline bool tek_ok(int T, int E, int k) {
     return T >= 0 && E >= 1 && E <= MOE_MAX_E && k >= 1 && k <= MOE_MAX_K && k <= E &&
@@ -78,8 +83,10 @@ size_t moe_expert_ffn_workspace(int N, int E, int d, int f, moe_dtype_t act_dtyp
     size_t need = moe_ffn_f32_workspace(N, E, d, f);
     const size_t s = moe_ffn_stream_workspace(N, E, d, f);
     const size_t g = moe_ffn_grouped_workspace(N, E, d, f);
+    const size_t m = moe_ffn_mid_workspace(N, E, d, f);
     if (s > need) need = s;
     if (g > need) need = g;
+    if (m > need) need = m;
     return align256(need) + 256;
 }
 
@@ -88,7 +95,8 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
                         float* yg, int path, void* stream) {
     if (!W || N < 0 || N >= MOE_MAX_N) return MOE_ERR_INVALID_ARG;
     if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
-    if (path != MOE_FFN_AUTO && path != MOE_FFN_STREAM && path != MOE_FFN_GROUPED)
+    if (path != MOE_FFN_AUTO && path != MOE_FFN_STREAM && path != MOE_FFN_GROUPED &&
+        path != MOE_FFN_MID)
         return MOE_ERR_INVALID_ARG;
     if (!offsets) return MOE_ERR_INVALID_ARG;
     if (N == 0) return MOE_OK;
@@ -103,14 +111,24 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
         return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
     }
     if (path == MOE_FFN_AUTO) {
-        // Few routed rows: the layer is weight-bandwidth bound and the streaming kernels
-        // read each active expert once per 16-row tile at ~6 TB/s.  Measured crossover with
-        // the grouped kernels (Mixtral shape, Zipf-skewed routing): between 96 and 128 rows.
-        path = (N <= 96 && moe_ffn_stream_supported(W->d, W->f)) ? MOE_FFN_STREAM
-                                                                   : MOE_FFN_GROUPED;
+        // Measured crossovers (Mixtral shape, Zipf-skewed routing):
+        //   up to 72 routed rows the decode kernels, which stream each active expert once
+        //   per 16-row tile at ~6 TB/s;
+        //   up to MOE_MID_MAX_ROWS rows per expert on average the weight-streaming grouped
+        //   GEMM (every expert's matrices are read about once, many row blocks per read);
+        //   above that the LDS-tiled grouped GEMM.
+        if (N <= 72 && moe_ffn_stream_supported(W->d, W->f))
+            path = MOE_FFN_STREAM;
+        else if ((long long)N <= (long long)MOE_MID_MAX_ROWS * W->E &&
+                 moe_ffn_mid_supported(N, W->E, W->d, W->f))
+            path = MOE_FFN_MID;
+        else
+            path = MOE_FFN_GROUPED;
     }
     if (path == MOE_FFN_STREAM)
         return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
+    if (path == MOE_FFN_MID)
+        return moe_ffn_mid_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
     return moe_ffn_grouped_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
 }
 

@@ -40,6 +40,7 @@
 //     expert, then feature tile, then token tile, one contiguous eighth of that
 //     order per XCD.
 #include "moe_internal.h"
+#include "moe_frag_pack.h"
 
 // Tile shapes (token blocks of 16 rows x weight fragment rows of 16 features per workgroup;
 // a wave owns all token blocks x FRW = fragment rows / 4; 64 MFMA tiles per wave either way):
@@ -48,82 +49,15 @@
 //           tile is half empty -- twice the weight bytes per step, no padded matrix work.
 #define GG_THREADS 256
 #define GG_NS 8            // LDS stages of B fragments (one KiB per token block each)
-// The weight fragments of step k are requested LA steps earlier into a register ring that
-// is named statically, so the step loop is unrolled U times (LA < U, reduction % U == 0).
-// Two variants: U = 4, LA = 3 (the default) and U = 8, LA = 5 with the matrix instructions
-// of empty row quarters skipped, for launches with few rows per expert, which are bound by
-// the weight stream from HBM and gain from more bytes in flight (5 is what the 8 LDS
-// stages allow, see the waits in the step).
-#define GG_U_MIN 4
+// The weight fragments of step k are requested GG_LA steps earlier into a register ring that
+// is named statically, so the step loop is unrolled GG_U times (GG_LA < GG_U, reduction %
+// GG_U == 0; GG_LA <= GG_NS - 3, see the waits in the step).  A deeper ring (8 / 5) measured
+// no faster.
+#define GG_U 4
+#define GG_LA 3
 #ifndef GG_WIDE_MAX_ROWS
 #define GG_WIDE_MAX_ROWS 96  // mean rows per expert up to which the 128 x 512 tile is used
 #endif
-#ifndef GG_RAGGED_VARIANT
-#define GG_RAGGED_VARIANT 1
-#endif
-
-// ---- segment bookkeeping: expert e owns blocks [bbase_e, bbase_e + ceil(M_e/16)) ----
-struct SegInfo {
-    int e;        // expert
-    int row0;     // first row of the expert's segment in xg / yg
-    int rows;     // rows of the segment
-    int bbase;    // first packed block of the segment
-};
-
-__device__ __forceinline__ int gg_clamp_off(int v, int lo, int N) {
-    return v < lo ? lo : (v > N ? N : v);
-}
-
-// Locate packed block `blk` (global block index) -> its segment; false if past the end.
-__device__ __forceinline__ bool gg_find_block(const int32_t* __restrict__ offsets, int E, int N,
-                                              int blk, SegInfo& si) {
-    int bb = 0, prev = 0;
-    for (int e = 0; e < E; e++) {
-        const int lo = gg_clamp_off(offsets[e], prev, N);
-        const int hi = gg_clamp_off(offsets[e + 1], lo, N);
-        prev = lo;
-        const int nb = (hi - lo + 15) / 16;
-        if (blk < bb + nb) {
-            si.e = e; si.row0 = lo; si.rows = hi - lo; si.bbase = bb;
-            return true;
-        }
-        bb += nb;
-    }
-    return false;
-}
-
-// ------------------------------------------------------------------- pack ----
-// One workgroup per packed block: rows [row0 + 16*b, +16) of a segment become
-// d/32 B-operand fragments; rows past the segment end are zero.
-template <bool ACT_BF16>
-__global__ __launch_bounds__(256) void gg_pack_kernel(const void* __restrict__ xg,
-                                                      const int32_t* __restrict__ offsets, int E,
-                                                      int N, int d, u32x4_t* __restrict__ xp) {
-    SegInfo si;
-    if (!gg_find_block(offsets, E, N, blockIdx.x, si)) return;
-    const int b = blockIdx.x - si.bbase;
-    const int KS = d / 32;
-    for (int i = threadIdx.x; i < KS * 64; i += 256) {
-        const int lane = i & 63, ks = i >> 6;
-        const int t = lane & 15, kq = lane >> 4;
-        const int r = b * 16 + t;
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (r < si.rows) {
-            const size_t off = (size_t)(si.row0 + r) * d + (size_t)ks * 32 + kq * 8;
-            if (ACT_BF16) {
-                v = *(const u32x4_t*)((const uint16_t*)xg + off);
-            } else {
-                const float4 v0 = *(const float4*)((const float*)xg + off);
-                const float4 v1 = *(const float4*)((const float*)xg + off + 4);
-                v[0] = moe_pack_bf16x2(v0.x, v0.y);
-                v[1] = moe_pack_bf16x2(v0.z, v0.w);
-                v[2] = moe_pack_bf16x2(v1.x, v1.y);
-                v[3] = moe_pack_bf16x2(v1.z, v1.w);
-            }
-        }
-        xp[((size_t)blockIdx.x * KS + ks) * 64 + lane] = v;
-    }
-}
 
 // ------------------------------------------------------------------- GEMM ----
 struct GroupedArgs {
@@ -224,43 +158,6 @@ __device__ __forceinline__ void gg_mfma(f32x4_t& c, const u32x4_t& a, const bf16
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
-// The 16 MFMAs of four token blocks (one quarter of the tile's rows), skipped as a whole
-// when those blocks lie beyond the last occupied one (quad >= nquads).  The branch sits
-// inside the asm statement so that the compiler keeps seeing one straight-line step: with
-// a branch of its own around matrix instructions it drains every counter at the borders.
-__device__ __forceinline__ void gg_mfma_quad(f32x4_t (&c0)[4], f32x4_t (&c1)[4], f32x4_t (&c2)[4],
-                                             f32x4_t (&c3)[4], const u32x4_t (&a)[4],
-                                             const bf16x8_t& b0, const bf16x8_t& b1,
-                                             const bf16x8_t& b2, const bf16x8_t& b3, int nquads,
-                                             const int quad) {
-    asm volatile(
-        "s_cmp_gt_i32 %24, %25\n\t"
-        "s_cbranch_scc0 1f\n\t"
-        "v_mfma_f32_16x16x32_bf16 %0, %16, %20, %0\n\t"
-        "v_mfma_f32_16x16x32_bf16 %1, %17, %20, %1\n\t"
-        "v_mfma_f32_16x16x32_bf16 %2, %18, %20, %2\n\t"
-        "v_mfma_f32_16x16x32_bf16 %3, %19, %20, %3\n\t"
-        "v_mfma_f32_16x16x32_bf16 %4, %16, %21, %4\n\t"
-        "v_mfma_f32_16x16x32_bf16 %5, %17, %21, %5\n\t"
-        "v_mfma_f32_16x16x32_bf16 %6, %18, %21, %6\n\t"
-        "v_mfma_f32_16x16x32_bf16 %7, %19, %21, %7\n\t"
-        "v_mfma_f32_16x16x32_bf16 %8, %16, %22, %8\n\t"
-        "v_mfma_f32_16x16x32_bf16 %9, %17, %22, %9\n\t"
-        "v_mfma_f32_16x16x32_bf16 %10, %18, %22, %10\n\t"
-        "v_mfma_f32_16x16x32_bf16 %11, %19, %22, %11\n\t"
-        "v_mfma_f32_16x16x32_bf16 %12, %16, %23, %12\n\t"
-        "v_mfma_f32_16x16x32_bf16 %13, %17, %23, %13\n\t"
-        "v_mfma_f32_16x16x32_bf16 %14, %18, %23, %14\n\t"
-        "v_mfma_f32_16x16x32_bf16 %15, %19, %23, %15\n\t"
-        "1:"
-        : "+a"(c0[0]), "+a"(c0[1]), "+a"(c0[2]), "+a"(c0[3]), "+a"(c1[0]), "+a"(c1[1]),
-          "+a"(c1[2]), "+a"(c1[3]), "+a"(c2[0]), "+a"(c2[1]), "+a"(c2[2]), "+a"(c2[3]),
-          "+a"(c3[0]), "+a"(c3[1]), "+a"(c3[2]), "+a"(c3[3])
-        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(b0), "v"(b1), "v"(b2), "v"(b3),
-          "s"(nquads), "i"(quad)
-        : "scc");
-}
-
 // Global source pointers of one tile for this wave (all wave-uniform).
 template <int FRW, int NBQ>
 struct TileSrc {
@@ -288,10 +185,10 @@ __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo
 // takes two launches, because an epilogue with both the SiLU*mul body and the raw store of
 // partial sums makes the compiler spill ~150 accumulators per tile).
 // NBW x FRW: token blocks of the tile x fragment rows of a wave (16 x 4 or 8 x 8).
-template <bool UP, int NBW, int FRW, int U, int LA, bool SKIP, int MODE>  // LA < U, LA <= GG_NS - 3
+template <bool UP, int NBW, int FRW, int MODE>
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     static_assert(NBW * FRW == 64 && NBW % 4 == 0, "64 MFMA tiles per wave");
-    static_assert(!SKIP || (NBW == 16 && FRW == 4), "quarter skipping is written for 16 x 4");
+    constexpr int U = GG_U, LA = GG_LA;
     constexpr int FROWS = 4 * FRW;     // fragment rows of the workgroup tile
     constexpr int NBQ = NBW / 4;       // token blocks each wave requests into LDS per step
     constexpr int VREQ = FRW + NBQ;    // vector-memory requests per wave and step
@@ -410,8 +307,6 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         // One reduction step.  Ac: weight fragments of this step; An: ring slot that
         // receives the fragments of step k+LA.  fast: every look-ahead lies inside
         // the current tile, so there is nothing to decide (compile-time after inlining).
-        // quarters of the tile's rows that hold tokens (SKIP: the others do no arithmetic)
-        const int nquads = __builtin_amdgcn_readfirstlane((cur.nblk + 3) >> 2);
         auto step = [&](int k, u32x4_t(&Ac)[FRW], u32x4_t(&An)[FRW], const bool fast) {
             // do the look-ahead requests exist (in this tile or the next one)?
             const bool la_b = fast || has_next || (k + GG_NS - 1 < KT);
@@ -452,38 +347,20 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
                             An[v - NBQ] = *a_src(v - NBQ, k + LA);
                     }
             };
-            if constexpr (!SKIP) {
 #pragma unroll
-                for (int i = 0; i < NBW; i++) {
-                    // the vector-memory requests are spread evenly over the blocks (one per
-                    // 8 MFMAs for 16 x 4), so that the requests of the four waves never
-                    // queue up in front of the matrix instructions
+            for (int i = 0; i < NBW; i++) {
+                // the vector-memory requests are spread evenly over the blocks (one per
+                // 8 MFMAs for 16 x 4), so that the requests of the four waves never
+                // queue up in front of the matrix instructions
 #pragma unroll
-                    for (int v = (i * VREQ + NBW - 1) / NBW; v < ((i + 1) * VREQ + NBW - 1) / NBW; v++)
-                        issue(v);
-                    // LDS reads return in order: with at most NBW-2 younger ones in flight,
-                    // breg[i] and breg[i+1] (refilled one step ago) have arrived
-                    if ((i & 1) == 0) GG_WAIT_LGKM(NBW - 2);
+                for (int v = (i * VREQ + NBW - 1) / NBW; v < ((i + 1) * VREQ + NBW - 1) / NBW; v++)
+                    issue(v);
+                // LDS reads return in order: with at most NBW-2 younger ones in flight,
+                // breg[i] and breg[i+1] (refilled one step ago) have arrived
+                if ((i & 1) == 0) GG_WAIT_LGKM(NBW - 2);
 #pragma unroll
-                    for (int j = 0; j < FRW; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
-                    if (more) breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
-                }
-            } else {
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    issue(2 * q);
-                    issue(2 * q + 1);
-                    // with at most 12 younger LDS reads in flight, breg[4q..4q+3] have arrived
-                    GG_WAIT_LGKM(12);
-                    gg_mfma_quad(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3], Ac,
-                                 breg[4 * q], breg[4 * q + 1], breg[4 * q + 2], breg[4 * q + 3],
-                                 nquads, q);
-                    if (more) {
-#pragma unroll
-                        for (int i = 4 * q; i < 4 * q + 4; i++)
-                            breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
-                    }
-                }
+                for (int j = 0; j < FRW; j++) gg_mfma(acc[i][j], Ac[j], breg[i]);
+                if (more) breg[i] = __builtin_bit_cast(bf16x8_t, pb[i * 64]);
             }
             g++;
         };
@@ -728,15 +605,12 @@ size_t moe_ffn_grouped_workspace(int N, int E, int d, int f) {
 }
 
 // Kernel variants by rows per expert (see the tile shapes at the top of the file).
-enum GgVariant { GG_STD = 0, GG_FEW = 1, GG_WIDE = 2 };
+enum GgVariant { GG_STD = 0, GG_WIDE = 1 };
 
 template <bool UP, int MODE>
 static const void* gg_kernel_ptr(GgVariant v) {
-    switch (v) {
-        case GG_FEW: return (const void*)gg_gemm_kernel<UP, 16, 4, 8, 5, true, MODE>;
-        case GG_WIDE: return (const void*)gg_gemm_kernel<UP, 8, 8, 4, 3, false, MODE>;
-        default: return (const void*)gg_gemm_kernel<UP, 16, 4, 4, 3, false, MODE>;
-    }
+    return v == GG_WIDE ? (const void*)gg_gemm_kernel<UP, 8, 8, MODE>
+                        : (const void*)gg_gemm_kernel<UP, 16, 4, MODE>;
 }
 
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
@@ -746,21 +620,15 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     // down tile = 256 features: d % 256 == 0; both give reductions of >= 8 steps, step
     // counts that are multiples of 4.
     if (f % 128 != 0 || d % 256 != 0) return MOE_ERR_UNSUPPORTED;
-    // the step loop is unrolled 4 or 8 times and looks GG_NS-1 steps ahead
-    if ((d / 32) % GG_U_MIN != 0 || (f / 32) % GG_U_MIN != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
+    // the step loop is unrolled GG_U times and looks GG_NS-1 steps ahead
+    if ((d / 32) % GG_U != 0 || (f / 32) % GG_U != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
         return MOE_ERR_UNSUPPORTED;
     // Variant by the mean number of rows per expert (the host never sees the real counts):
-    //   <= 40:  default tile, steps unrolled 8x, weights 5 steps ahead, empty row quarters
-    //           skipped (5-10 % faster than the default up to 32 rows, slower from 64 on);
-    //   <= GG_WIDE_MAX_ROWS: 128-token x 512-feature tile (needs f % 256 == 0 for the first
-    //           projection, d % 512 == 0 for the second; each falls back on its own);
-    //   else:   default.
+    // up to GG_WIDE_MAX_ROWS the 128-token x 512-feature tile (needs f % 256 == 0 for the
+    // first projection, d % 512 == 0 for the second; each falls back on its own).
     const long long mean_rows = ((long long)N + E - 1) / E;
     GgVariant vu = GG_STD, vd = GG_STD;
-    if (GG_RAGGED_VARIANT && mean_rows <= 40) {
-        if ((d / 32) % 8 == 0) vu = GG_FEW;
-        if ((f / 32) % 8 == 0) vd = GG_FEW;
-    } else if (mean_rows <= GG_WIDE_MAX_ROWS) {
+    if (mean_rows <= GG_WIDE_MAX_ROWS) {
         if (f % 256 == 0) vu = GG_WIDE;
         if (d % 512 == 0) vd = GG_WIDE;
     }
@@ -772,7 +640,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
 
     static bool attr_set = false;
     if (!attr_set) {
-        for (int v = 0; v < 3; v++) {
+        for (int v = 0; v < 2; v++) {
             const void* all[3] = {gg_kernel_ptr<true, 1>((GgVariant)v), gg_kernel_ptr<true, 2>((GgVariant)v),
                                   gg_kernel_ptr<false, 0>((GgVariant)v)};
             for (int i = 0; i < 3; i++)
@@ -814,7 +682,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     {
         void* params[1] = {(void*)&up};
         const size_t lds_bytes = (size_t)GG_NS * up.TB * MOE_FRAG_BYTES;
-        const int unit = vu == GG_FEW ? 8 : 4;
+        const int unit = GG_U;
         MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 1>(vu), dim3(pgrid), dim3(GG_THREADS), params,
                                     lds_bytes, s));
         if (up.split) {
@@ -849,7 +717,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     {
         void* params[1] = {(void*)&dn};
         const size_t lds_bytes = (size_t)GG_NS * dn.TB * MOE_FRAG_BYTES;
-        const int unit = vd == GG_FEW ? 8 : 4;
+        const int unit = GG_U;
         MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<false, 0>(vd), dim3(pgrid), dim3(GG_THREADS), params,
                                     lds_bytes, s));
         if (dn.split) {

@@ -73,6 +73,11 @@ size_t moe_ffn_grouped_workspace(int N, int E, int d, int f);
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
                            const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
 
+bool moe_ffn_mid_supported(int N, int E, int d, int f);
+size_t moe_ffn_mid_workspace(int N, int E, int d, int f);
+int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
+                       const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
+
 // ---- small device helpers ------------------------------------------------------
 #ifdef __HIPCC__
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));

@@ -175,6 +175,29 @@ def test_layer_bf16_grouped_path(moe, T, d, f, E, k, xdt):
     _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16, path=moe.MOE_FFN_GROUPED)
 
 
+@pytest.mark.parametrize("T,d,f,E,k,xdt", [
+    (1, 256, 512, 8, 2, mi.F32), (16, 256, 512, 8, 2, mi.BF16), (100, 256, 512, 8, 2, mi.BF16),
+    (300, 512, 1024, 8, 2, mi.F32), (700, 256, 384, 4, 2, mi.BF16), (260, 1024, 2048, 16, 2, mi.F32),
+    (150, 512, 2304, 8, 2, mi.BF16), (500, 256, 4096, 2, 1, mi.BF16)])
+def test_layer_bf16_mid_path(moe, T, d, f, E, k, xdt):
+    """Weight-streaming grouped GEMM: experts of 0 to several hundred rows (several 192-row
+    tiles), 4/8/12-block bodies, one and several reduction parts in the second projection."""
+    cfg = mi.small_config("md", T, d, f, E, k, 700 + T + d, w_dtype=mi.BF16, x_dtype=xdt,
+                          zipf_s=1.2)
+    _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16, path=moe.MOE_FFN_MID)
+
+
+def test_mid_path_is_deterministic(moe):
+    cfg = mi.small_config("mdd", 200, 256, 4096, 4, 2, 771, w_dtype=mi.BF16, x_dtype=mi.BF16,
+                          zipf_s=1.2)
+    li = mi.make_layer(cfg, threads=1)
+    W = pack_layer(li)
+    outs = [to_host(moe.moe_layer(W, to_dev(li.x), to_dev(li.logits), cfg.k,
+                                  path=moe.MOE_FFN_MID)["yg"]) for _ in range(3)]
+    assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all()
+    W.free()
+
+
 def test_ffn_rejects_short_workspace_and_bad_path(moe):
     cfg = mi.small_config("ws", 4, 256, 512, 8, 2, 9, w_dtype=mi.BF16)
     li = mi.make_layer(cfg, threads=1)
@@ -229,8 +252,10 @@ def test_all_tokens_to_one_expert_and_k_equals_E(moe, path_name, T, xdt):
 def test_single_expert_layer_and_auto_threshold(moe):
     cfg = mi.small_config("E1", 9, 256, 512, 1, 1, 77, w_dtype=mi.BF16)
     _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16)
-    # AUTO on either side of the stream/grouped switch (96 routed rows)
-    for T in (48, 49):
+    # AUTO on either side of its switches: decode kernels up to 72 routed rows, the
+    # weight-streaming grouped GEMM up to 40 rows per expert (320 rows here), then the
+    # LDS-tiled grouped GEMM (128 x 512 tile up to 96 rows per expert, 256 x 256 above)
+    for T in (36, 37, 160, 161, 384, 385):
         cfg = mi.small_config("thr", T, 256, 512, 8, 2, 80 + T, w_dtype=mi.BF16, zipf_s=1.2)
         _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16)
 
