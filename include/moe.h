@@ -154,11 +154,16 @@ int moe_combine(const float* yg, const int32_t* inv_perm, const float* weights, 
  *   moe_rmsnorm:       h[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + eps)    fp32 [T,d]
  *   moe_router_logits: logits[t,e] = sum_r h[t,r] * w_gate[r,e]        w_gate [d,E] fp32
  *   moe_residual_add:  x[t,:] += y[t,:]                                in place
+ *   moe_rmsnorm_router_logits: both of the first two in one launch, any T, E <= 16
+ *                      (MOE_ERR_UNSUPPORTED above); logits = (x . w_gate) / rms(x) in fp32,
+ *                      i.e. the normalisation is applied after the dot product.
  */
 int moe_rmsnorm(const float* x, int T, int d, float eps, float* h, void* stream);
 int moe_router_logits(const float* h, const float* w_gate, int T, int d, int E, float* logits,
                       void* stream);
 int moe_residual_add(float* x, const float* y, int T, int d, void* stream);
+int moe_rmsnorm_router_logits(const float* x, const float* w_gate, int T, int d, int E, float eps,
+                              float* h, float* logits, void* stream);
 
 /*
  * Fused front ends for decode-sized batches: the same results as the separate calls, in

@@ -9,7 +9,7 @@ from .binding import (StackBuffers, moe_route_permute, moe_norm_route_permute,
                       moe_combine_residual, moe_combine_norm_route_permute, moe_mfma_rate_probe, moe_stack_forward, MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID, MOE_FFN_STREAM,
                       MoeError, PackedWeights, lib, lib_path, moe_combine, moe_expert_ffn,
                       moe_expert_ffn_workspace, moe_layer, moe_permute, moe_residual_add,
-                      moe_rmsnorm, moe_route, moe_router_logits, moe_set_ffn_mid_event,
+                      moe_rmsnorm, moe_rmsnorm_router_logits, moe_route, moe_router_logits, moe_set_ffn_mid_event,
                       moe_status_string,
                       moe_weights_free, moe_weights_pack)
 
@@ -19,6 +19,6 @@ __all__ = [
     "MOE_BF16", "MOE_F32", "MOE_FFN_AUTO", "MOE_FFN_GROUPED", "MOE_FFN_MID", "MOE_FFN_STREAM", "MoeError",
     "PackedWeights", "lib", "lib_path", "moe_combine", "moe_expert_ffn",
     "moe_expert_ffn_workspace", "moe_layer", "moe_permute", "moe_residual_add", "moe_rmsnorm",
-    "moe_route", "moe_router_logits", "moe_set_ffn_mid_event", "moe_status_string", "moe_weights_free",
+    "moe_rmsnorm_router_logits", "moe_route", "moe_router_logits", "moe_set_ffn_mid_event", "moe_status_string", "moe_weights_free",
     "moe_weights_pack",
 ]

@@ -21,7 +21,8 @@ EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
            "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
            "moe_mfma_rate_probe", "moe_route_permute", "moe_norm_route_permute",
-           "moe_combine_residual", "moe_combine_norm_route_permute")
+           "moe_combine_residual", "moe_combine_norm_route_permute",
+           "moe_rmsnorm_router_logits")
 
 
 class MoeError(RuntimeError):
@@ -60,6 +61,8 @@ def lib():
         L.moe_rmsnorm.argtypes = [vp, i32, i32, f32, vp, vp]
         L.moe_router_logits.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.moe_residual_add.argtypes = [vp, vp, i32, i32, vp]
+        L.moe_rmsnorm_router_logits.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp]
+        L.moe_rmsnorm_router_logits.restype = C.c_int
         L.moe_set_ffn_mid_event.argtypes = [vp]
         L.moe_set_ffn_mid_event.restype = C.c_int
         L.moe_mfma_rate_probe.argtypes = [vp, i32, vp, C.POINTER(C.c_double), vp]
@@ -253,6 +256,22 @@ def moe_router_logits(h: torch.Tensor, w_gate: torch.Tensor, logits=None, stream
     return logits
 
 
+def moe_rmsnorm_router_logits(x: torch.Tensor, w_gate: torch.Tensor, eps: float = 1e-5, h=None,
+                              logits=None, stream=None):
+    """h = rmsnorm(x) and logits = h . w_gate in one launch (E <= 16)."""
+    _dev(x, torch.float32, "x")
+    T, d = x.shape
+    E = w_gate.shape[1]
+    if h is None:
+        h = torch.empty_like(x)
+    if logits is None:
+        logits = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    _check(lib().moe_rmsnorm_router_logits(_ptr(x), _ptr(w_gate), T, d, E, eps, _ptr(h),
+                                           _ptr(logits), _stream(stream)),
+           "moe_rmsnorm_router_logits")
+    return h, logits
+
+
 def moe_residual_add(x: torch.Tensor, y: torch.Tensor, stream=None):
     _dev(x, torch.float32, "x")
     _dev(y, torch.float32, "y")
@@ -394,8 +413,11 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
                                    rs["perm_out"], stream=stream)
             _, offsets, _, inv_perm, xg = rs["perm_out"]
         else:
-            moe_rmsnorm(cur, eps, bufs.h, stream=stream)
-            moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
+            if fused and W0.E <= 16:
+                moe_rmsnorm_router_logits(cur, w_gate, eps, bufs.h, bufs.logits, stream=stream)
+            else:
+                moe_rmsnorm(cur, eps, bufs.h, stream=stream)
+                moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
             moe_route(bufs.logits, k, rs["idx"], rs["w"], stream=stream)
             _, offsets, _, inv_perm, xg = moe_permute(rs["idx"], W.E, bufs.h, out=rs["perm_out"],
                                                       stream=stream)

@@ -161,7 +161,20 @@ int moe_router_logits(const float* h, const float* w_gate, int T, int d, int E, 
     if (T < 0 || !dims_ok(d) || E < 1 || E > MOE_MAX_E) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!h || !w_gate || !logits) return MOE_ERR_INVALID_ARG;
+    if (moe_norm_logits_supported(E) && moe_aligned16(h))
+        return moe_norm_logits_launch(false, h, w_gate, T, d, E, 0.f, nullptr, logits,
+                                      (hipStream_t)stream);
     return moe_router_logits_launch(h, w_gate, T, d, E, logits, (hipStream_t)stream);
+}
+
+int moe_rmsnorm_router_logits(const float* x, const float* w_gate, int T, int d, int E, float eps,
+                              float* h, float* logits, void* stream) {
+    if (T < 0 || !dims_ok(d) || E < 1 || E > MOE_MAX_E || !(eps >= 0.f)) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !w_gate || !h || !logits || !moe_aligned16(x) || !moe_aligned16(h))
+        return MOE_ERR_INVALID_ARG;
+    if (!moe_norm_logits_supported(E)) return MOE_ERR_UNSUPPORTED;
+    return moe_norm_logits_launch(true, x, w_gate, T, d, E, eps, h, logits, (hipStream_t)stream);
 }
 
 int moe_residual_add(float* x, const float* y, int T, int d, void* stream) {

@@ -109,6 +109,9 @@ int moe_rmsnorm_launch(const float* x, int T, int d, float eps, float* h, hipStr
 int moe_router_logits_launch(const float* h, const float* w_gate, int T, int d, int E,
                              float* logits, hipStream_t s);
 int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t s);
+bool moe_norm_logits_supported(int E);
+int moe_norm_logits_launch(bool norm, const float* x, const float* w_gate, int T, int d, int E,
+                           float eps, float* h, float* logits, hipStream_t s);
 int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E, int d, int f,
                           moe_dtype_t w_dtype, moe_weights** out, hipStream_t s);
 int moe_weights_free_impl(moe_weights* W);

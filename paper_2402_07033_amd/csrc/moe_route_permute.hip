@@ -403,7 +403,7 @@ int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t 
 #define GATE_MAX_T 16       // tokens the fused gate handles
 #define GATE_NORM_MAX_T 4   // ... when it also normalises and computes the router logits
 #define GATE_MAX_E 16
-// Partial sums of one thread for the fused RMSNorm + router: rows r = tid + i * PERM_THREADS.
+// Partial sums of one thread for the fused RMSNorm + router: rows r = tid + i * STRIDE.
 // TT = tokens handled (compile-time bound on T), UNR = rows whose loads are in flight together.
 // The pending combine + residual of the block before (COMB): the row values are
 //   x[t,r] + sum_j w_prev[t,j] * yg_prev[pos_prev[t,j], r]
@@ -415,7 +415,7 @@ struct GatePrev {
     int k;
 };
 
-template <int TT, int UNR, int KJMAX>
+template <int TT, int UNR, int KJMAX, int STRIDE = PERM_THREADS>
 __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
                                                   const float* __restrict__ w_gate, int T, int d,
                                                   int E, int tid, const GatePrev& pv,
@@ -424,11 +424,11 @@ __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
     constexpr bool COMB = KJMAX > 0;        // KJMAX: compile-time bound on pv.k (0: no combine)
     constexpr int KJ = COMB ? KJMAX : 1;
     const bool vec = (E & 3) == 0;  // rows of w_gate are then 16-byte aligned
-    for (int r0 = tid; r0 < d; r0 += UNR * PERM_THREADS) {
+    for (int r0 = tid; r0 < d; r0 += UNR * STRIDE) {
         float wr[UNR][GATE_MAX_E], xv[UNR][TT], yv[UNR][TT][KJ];
 #pragma unroll
         for (int u = 0; u < UNR; u++) {
-            const int r = r0 + u * PERM_THREADS;
+            const int r = r0 + u * STRIDE;
 #pragma unroll
             for (int e = 0; e < GATE_MAX_E; e++) wr[u][e] = 0.f;
 #pragma unroll
@@ -750,5 +750,98 @@ int moe_combine_residual_launch(const float* yg, const int32_t* inv_perm, const 
                            inv_perm + (size_t)t0 * k, weights + (size_t)t0 * k, tn, k, row_chunks,
                            (float4*)(x + (size_t)t0 * d));
     }
+    return moe_launch_status();
+}
+
+// ------------------------------- RMSNorm + router logits for any number of tokens ----
+// NL_TOK tokens per workgroup of 1024 threads, so that a row of the router matrix is loaded
+// once for NL_TOK tokens; thread-strided partial sums with grouped loads (see
+// gate_partial_sums), reduced over the workgroup.  NORM: h = x / rms(x) is written and
+// logits = (x . w_gate) / rms(x); else logits = x . w_gate.  E <= GATE_MAX_E.
+#define NL_TOK 2
+#define NL_THREADS 1024
+template <bool NORM>
+__global__ __launch_bounds__(NL_THREADS) void norm_logits_kernel(const float* __restrict__ x,
+                                                                  const float* __restrict__ w_gate,
+                                                                  int T, int d, int E, float eps,
+                                                                  float* __restrict__ h,
+                                                                  float* __restrict__ logits) {
+    static_assert(NL_TOK <= GATE_NORM_MAX_T, "gate_partial_sums holds GATE_NORM_MAX_T tokens");
+    __shared__ float s_part[NL_THREADS / 64][NL_TOK * (GATE_MAX_E + 1)];
+    __shared__ float s_inv[NL_TOK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * NL_TOK;
+    const int Tl = (T - t0) < NL_TOK ? (T - t0) : NL_TOK;
+    const float* xb = x + (size_t)t0 * d;
+    float ss[GATE_NORM_MAX_T], acc[GATE_NORM_MAX_T][GATE_MAX_E];
+#pragma unroll
+    for (int t = 0; t < NL_TOK; t++) {
+        ss[t] = 0.f;
+#pragma unroll
+        for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = 0.f;
+    }
+    const GatePrev none = {nullptr, nullptr, nullptr, 0};
+    gate_partial_sums<NL_TOK, 4, 0, NL_THREADS>(xb, w_gate, Tl, d, E, tid, none, ss, acc);
+#pragma unroll
+    for (int t = 0; t < NL_TOK; t++) {
+        if (t < Tl) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) ss[t] += __shfl_xor(ss[t], m, 64);
+#pragma unroll
+            for (int e = 0; e < GATE_MAX_E; e++) {
+                if (e < E) {
+#pragma unroll
+                    for (int m = 32; m >= 1; m >>= 1) acc[t][e] += __shfl_xor(acc[t][e], m, 64);
+                }
+            }
+            if (lane == 0) {
+                s_part[wave][t * (GATE_MAX_E + 1) + GATE_MAX_E] = ss[t];
+#pragma unroll
+                for (int e = 0; e < GATE_MAX_E; e++)
+                    if (e < E) s_part[wave][t * (GATE_MAX_E + 1) + e] = acc[t][e];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < Tl) {
+        float v = 0.f;
+        for (int w = 0; w < NL_THREADS / 64; w++) v += s_part[w][tid * (GATE_MAX_E + 1) + GATE_MAX_E];
+        s_inv[tid] = NORM ? 1.0f / sqrtf(v / (float)d + eps) : 1.0f;
+    }
+    __syncthreads();
+    if (tid < Tl * GATE_MAX_E) {
+        const int t = tid / GATE_MAX_E, e = tid % GATE_MAX_E;
+        if (e < E) {
+            float v = 0.f;
+            for (int w = 0; w < NL_THREADS / 64; w++) v += s_part[w][t * (GATE_MAX_E + 1) + e];
+            logits[(size_t)(t0 + t) * E + e] = NORM ? v * s_inv[t] : v;
+        }
+    }
+    if (NORM) {
+        const int row_chunks = d / 4;
+        for (int t = 0; t < Tl; t++) {
+            const float sc = s_inv[t];
+            const float4* src = (const float4*)(xb + (size_t)t * d);
+            float4* dst = (float4*)(h + (size_t)(t0 + t) * d);
+            for (int c = tid; c < row_chunks; c += NL_THREADS) {
+                float4 v = src[c];
+                v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+                dst[c] = v;
+            }
+        }
+    }
+}
+
+bool moe_norm_logits_supported(int E) { return E <= GATE_MAX_E; }
+
+int moe_norm_logits_launch(bool norm, const float* x, const float* w_gate, int T, int d, int E,
+                           float eps, float* h, float* logits, hipStream_t s) {
+    const unsigned grid = (unsigned)((T + NL_TOK - 1) / NL_TOK);
+    if (norm)
+        hipLaunchKernelGGL(norm_logits_kernel<true>, dim3(grid), dim3(NL_THREADS), 0, s, x, w_gate, T,
+                           d, E, eps, h, logits);
+    else
+        hipLaunchKernelGGL(norm_logits_kernel<false>, dim3(grid), dim3(NL_THREADS), 0, s, x, w_gate, T,
+                           d, E, eps, h, logits);
     return moe_launch_status();
 }

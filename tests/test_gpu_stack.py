@@ -36,10 +36,22 @@ def test_support_kernels(moe):
         lg_ref = orc.router_logits(to_host(h).astype(np.float64), wg)
         lg = moe.moe_router_logits(h, to_dev(wg))
         assert np.max(np.abs(to_host(lg) - lg_ref)) <= 1e-5 * max(1.0, np.max(np.abs(lg_ref)))
+        # both in one launch: same h, logits = (x . w_gate) / rms(x) against the fp64 oracle
+        h2, lg2 = moe.moe_rmsnorm_router_logits(to_dev(x), to_dev(wg), 1e-5)
+        assert max_rel(to_host(h2), h_ref) <= 2e-6
+        lg_ref2 = orc.router_logits(h_ref, wg)
+        assert np.max(np.abs(to_host(lg2) - lg_ref2)) <= 2e-5 * max(1.0, np.max(np.abs(lg_ref2)))
         y = rng.standard_normal((T, d)).astype(np.float32)
         xd = to_dev(x)
         moe.moe_residual_add(xd, to_dev(y))
         assert (to_host(xd) == x + y).all()
+    # more than 16 experts: the separate kernels serve, the fused call says unsupported
+    x = to_dev(rng.standard_normal((5, 256)).astype(np.float32))
+    wg = to_dev((rng.standard_normal((256, 24)) / 16.0).astype(np.float32))
+    lg = moe.moe_router_logits(moe.moe_rmsnorm(x, 1e-5), wg)
+    assert lg.shape == (5, 24) and torch.isfinite(lg).all()
+    with pytest.raises(moe.MoeError):
+        moe.moe_rmsnorm_router_logits(x, wg, 1e-5)
 
 
 def test_fused_front_ends_match_separate_calls(moe):
