@@ -19,11 +19,14 @@
 //     run while the other waits for memory.
 //   up   : unit = (row tile, 16 fragment rows = 8 h-column blocks x (w1,w3)), full reduction,
 //          SiLU*mul in registers, h written as bf16 B-operand fragments for the second GEMM
-//   down : unit = (row tile, reduction part, 16 fragment rows = 256 features); with P > 1
-//          parts every unit stores its partial tile and mid_reduce_kernel adds the parts in
-//          a fixed order (deterministic, no atomics)
-// Units are dealt to the persistent workgroups in contiguous equal ranges, feature tile
-// fastest, so that a workgroup walks through neighbouring weight rows of one expert.
+//   down : unit = (row tile, 16 fragment rows = 256 features), yg fp32
+// The (unit, 4-step chunk) sequence of a launch, feature tile fastest, is cut into equal
+// contiguous shares, one per persistent workgroup, so that every workgroup streams the same
+// number of weight bytes whatever the unit count (896 first-projection units of the Mixtral
+// shape at 8 x 128 rows are 3.5 per CU; the 128 second-projection units half a unit per CU).
+// A workgroup that covers only a piece of a unit's reduction stores its partial sums and
+// mid_fixup_kernel adds the pieces of the unit in workgroup order (deterministic, no
+// atomics) and finishes it.
 #include "moe_internal.h"
 #include "moe_frag_pack.h"
 
@@ -32,6 +35,7 @@
 #define MD_KC 4          // reduction steps per LDS chunk
 #define MD_MAX_RB 12     // row blocks (of 16 rows) per row tile (192 rows)
 #define MD_BD 2          // LDS reads of B fragments kept ahead of the matrix instructions
+#define MD_MAX_PIECES 512 // workgroups of the GEMM launch (pieces a unit can have)
 #define MD_MAX_TILES 192 // row tiles per launch (N / 192 + E)
 
 struct MidArgs {
@@ -39,12 +43,11 @@ struct MidArgs {
     const u32x4_t* bfrag;  // packed activations (xp or hp)
     const int32_t* offsets;
     void* out;        // up: hp fragments (bf16); down: yg [N,d] fp32
-    float* part;      // down, P > 1: partial tiles [(tile * NT + ft) * P + part][16*MD_MAX_RB][256]
+    float* part;      // partial tiles of split units: [workgroup][2][16*MD_MAX_RB][256] fp32
     int E, N;
     int KS;      // reduction steps of 32
     int FR;      // weight fragment rows per expert (up: 2*f/16, down: d/16)
     int NT;      // feature tiles = FR / 16
-    int P;       // reduction parts (up: 1)
     int KS_out;  // up: f/32 (fragment columns of hp)
     int C;       // down: d (row length of yg)
 };
@@ -64,7 +67,7 @@ template <bool UP, int RBT>
 __device__ __forceinline__ void mid_unit(const MidArgs& a, u32x4_t* lds, const u32x4_t* wsrc,
                                          const u32x4_t* bsrc, int KP, int nblk, int wave, int lane,
                                          int e_row0, int e_rows, int bbase_blk, int blk0, int ft,
-                                         size_t slot) {
+                                         bool whole, size_t slot) {
     constexpr int NQ = RBT * MD_KC / MD_WAVES;  // direct-to-LDS requests per wave and chunk
     const int NCH = KP / MD_KC;
     f32x4_t acc[RBT][2];
@@ -183,7 +186,19 @@ __device__ __forceinline__ void mid_unit(const MidArgs& a, u32x4_t* lds, const u
 
     // ---- epilogue: D lane l holds rows 4*(l/16)+r (features) x column l%16 (token) ----
     const int t = lane & 15, fq = lane >> 4;
-    if (UP) {
+    if (!whole) {
+        // a piece of a unit's reduction: raw partial sums [row][16 fragment rows x 16] to this
+        // workgroup's scratch slot; mid_fixup_kernel adds the pieces of the unit
+        float* p0 = a.part + (slot * (16 * MD_MAX_RB) + t) * 256 + (2 * wave) * 16 + 4 * fq;
+#pragma unroll
+        for (int i = 0; i < RBT; i++) {
+            if (i >= nblk) continue;
+#pragma unroll
+            for (int m = 0; m < 2; m++)
+                *(float4*)(p0 + (size_t)i * 16 * 256 + m * 16) =
+                    make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
+        }
+    } else if (UP) {
         // fragment rows 2*wave (w1) and 2*wave+1 (w3) of the same 16 h-columns
         const int colblk = ft * 8 + wave;
         const int ks_o = colblk >> 1;
@@ -208,17 +223,31 @@ __device__ __forceinline__ void mid_unit(const MidArgs& a, u32x4_t* lds, const u
             if (i >= nblk) continue;
             const int r_in_seg = (blk0 + i) * 16 + t;
             if (r_in_seg >= e_rows) continue;
-            // one part: straight into yg; else this unit's partial tile (mid_reduce_kernel
-            // adds the parts in a fixed order) -- same code, only the destination differs
-            float* row = (a.P == 1)
-                             ? (float*)a.out + (size_t)(e_row0 + r_in_seg) * a.C + (ft * 16 + 2 * wave) * 16 + 4 * fq
-                             : a.part + (slot * (16 * MD_MAX_RB) + i * 16 + t) * 256 + (2 * wave) * 16 + 4 * fq;
+            float* row = (float*)a.out + (size_t)(e_row0 + r_in_seg) * a.C + (ft * 16 + 2 * wave) * 16 + 4 * fq;
 #pragma unroll
             for (int m = 0; m < 2; m++)
                 *(float4*)(row + m * 16) =
                     make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
         }
     }
+}
+
+// The launch's work is the sequence of (unit, chunk) pairs, unit = (row tile, feature tile),
+// chunk = MD_KC reduction steps; workgroup b of `grid` takes the pairs [cut(b), cut(b+1)), so
+// every workgroup streams the same number of weight bytes whatever the number of units.
+__device__ __forceinline__ long long mid_cut(long long G, int b, int grid) { return G * b / grid; }
+
+// Scratch slot of workgroup b's piece of unit u (or -1 if b finishes u alone / has no part
+// of it): its first unit's piece takes slot 0, its last unit's piece the next free one.
+__device__ __forceinline__ int mid_piece_slot(long long G, int NCH, int grid, int b, long long u) {
+    const long long gb = mid_cut(G, b, grid), ge = mid_cut(G, b + 1, grid);
+    const long long u_lo = u * NCH, u_hi = u_lo + NCH;
+    if (ge <= u_lo || gb >= u_hi || gb >= ge) return -1;
+    if (gb <= u_lo && ge >= u_hi) return -1;  // whole unit
+    const long long u_first = gb / NCH;
+    if (u == u_first) return 2 * b;
+    const bool head_partial = !((gb % NCH) == 0 && ge >= (u_first + 1) * NCH);
+    return 2 * b + (head_partial ? 1 : 0);
 }
 
 // Row tiles of the launch (<= MD_MAX_RB blocks of one expert each), listed in LDS by thread 0.
@@ -262,62 +291,109 @@ __global__ __launch_bounds__(MD_THREADS) void mid_kernel(MidArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     mid_tile_list(a.offsets, a.E, a.N, s_offs, s_te, s_blk0, s_nblk, s_row0, s_rows, s_bbase, &s_nt);
-    // unit index = (row tile * P + part) * NT + feature tile
-    const long long total = (long long)s_nt * a.P * a.NT;
-    const long long u_begin = total * blockIdx.x / gridDim.x;
-    const long long u_end = total * (blockIdx.x + 1) / gridDim.x;
-    const int KP = a.KS / a.P;
-    for (long long u = u_begin; u < u_end; ++u) {
+    // unit index = row tile * NT + feature tile
+    const int NCH = a.KS / MD_KC;
+    const long long G = (long long)s_nt * a.NT * NCH;
+    const long long g_end = mid_cut(G, blockIdx.x + 1, gridDim.x);
+    int piece = 0;
+    for (long long g = mid_cut(G, blockIdx.x, gridDim.x); g < g_end;) {
+        const long long u = g / NCH;
+        const int c0 = (int)(g % NCH);
+        const int nch = (int)((g_end - g) < (NCH - c0) ? (g_end - g) : (NCH - c0));
+        const bool whole = (nch == NCH);
         const int ft = (int)(u % a.NT);
-        const long long tp = u / a.NT;
-        const int part = (int)(tp % a.P);
-        const int tile = (int)(tp / a.P);
+        const int tile = (int)(u / a.NT);
         const int e = s_te[tile], blk0 = s_blk0[tile], nblk = s_nblk[tile];
-        const int k0 = part * KP;
+        const int k0 = c0 * MD_KC, KP = nch * MD_KC;
         const u32x4_t* wsrc =
             a.wfrag + (((size_t)e * a.FR + (size_t)ft * 16 + 2 * wave) * a.KS + k0) * 64 + lane;
         const u32x4_t* bsrc = a.bfrag + ((size_t)(s_bbase[e] + blk0) * a.KS + k0) * 64 + lane;
         const int row0 = s_row0[e], rows = s_rows[e], bbase = s_bbase[e];
-        const size_t slot = ((size_t)tile * a.NT + ft) * a.P + part;
+        const size_t slot = (size_t)blockIdx.x * 2 + piece;
+        if (!whole) piece++;
         if (nblk <= 4)
-            mid_unit<UP, 4>(a, lds, wsrc, bsrc, KP, nblk, wave, lane, row0, rows, bbase, blk0, ft, slot);
+            mid_unit<UP, 4>(a, lds, wsrc, bsrc, KP, nblk, wave, lane, row0, rows, bbase, blk0, ft, whole, slot);
         else if (nblk <= 8)
-            mid_unit<UP, 8>(a, lds, wsrc, bsrc, KP, nblk, wave, lane, row0, rows, bbase, blk0, ft, slot);
+            mid_unit<UP, 8>(a, lds, wsrc, bsrc, KP, nblk, wave, lane, row0, rows, bbase, blk0, ft, whole, slot);
         else
-            mid_unit<UP, 12>(a, lds, wsrc, bsrc, KP, nblk, wave, lane, row0, rows, bbase, blk0, ft, slot);
+            mid_unit<UP, 12>(a, lds, wsrc, bsrc, KP, nblk, wave, lane, row0, rows, bbase, blk0, ft, whole, slot);
+        g += nch;
     }
 }
 
-// yg rows of one (row tile, feature tile) = sum over the P partial tiles, in part order.
-// blockIdx.x = tile * NT + ft, blockIdx.y = group of 16 rows.
-__global__ __launch_bounds__(256) void mid_reduce_kernel(MidArgs a) {
+// Units whose reduction was shared by several workgroups: adds their pieces in workgroup
+// order (deterministic), then writes yg (second projection) or applies SiLU*mul and writes
+// the h fragments (first).  One workgroup per unit; `grid` = the GEMM launch's workgroup
+// count (<= MD_MAX_PIECES).
+template <bool UP>
+__global__ __launch_bounds__(256) void mid_fixup_kernel(MidArgs a, int grid) {
     __shared__ int s_te[MD_MAX_TILES], s_blk0[MD_MAX_TILES], s_nblk[MD_MAX_TILES];
     __shared__ int s_row0[MOE_MAX_E], s_rows[MOE_MAX_E], s_bbase[MOE_MAX_E];
     __shared__ int s_offs[MOE_MAX_E + 1];
     __shared__ int s_nt;
     mid_tile_list(a.offsets, a.E, a.N, s_offs, s_te, s_blk0, s_nblk, s_row0, s_rows, s_bbase, &s_nt);
-    const int tile = blockIdx.x / a.NT, ft = blockIdx.x % a.NT;
+    const long long u = blockIdx.x;
+    const int tile = (int)(u / a.NT), ft = (int)(u % a.NT);
     if (tile >= s_nt) return;
+    const int NCH = a.KS / MD_KC;
+    const long long G = (long long)s_nt * a.NT * NCH;
+    // workgroups that hold the unit's first and last chunk
+    const long long g_lo = u * NCH, g_hi = g_lo + NCH - 1;
+    int b_lo = (int)(g_lo * grid / G), b_hi = (int)(g_hi * grid / G);
+    while (b_lo > 0 && mid_cut(G, b_lo, grid) > g_lo) b_lo--;
+    while (b_lo + 1 < grid && mid_cut(G, b_lo + 1, grid) <= g_lo) b_lo++;
+    while (b_hi > 0 && mid_cut(G, b_hi, grid) > g_hi) b_hi--;
+    while (b_hi + 1 < grid && mid_cut(G, b_hi + 1, grid) <= g_hi) b_hi++;
+    if (b_lo == b_hi) return;  // one workgroup did the whole unit and wrote the result itself
+    // the pieces' scratch slots, in workgroup order (a unit has at most `grid` pieces)
+    __shared__ int s_slot[MD_MAX_PIECES];
+    const int nb = (b_hi - b_lo + 1) < MD_MAX_PIECES ? (b_hi - b_lo + 1) : MD_MAX_PIECES;
+    for (int i = threadIdx.x; i < nb; i += 256) s_slot[i] = mid_piece_slot(G, NCH, grid, b_lo + i, u);
+    __syncthreads();
     const int e = s_te[tile];
-    const int first = s_blk0[tile] * 16;                     // first row of the tile in its segment
-    int rows = s_rows[e] - first;                            // real rows of the tile
-    rows = rows < 16 * s_nblk[tile] ? rows : 16 * s_nblk[tile];
-    const int row_lo = blockIdx.y * 16;
-    if (row_lo >= rows) return;
-    const int nrow = (rows - row_lo) < 16 ? (rows - row_lo) : 16;
-    const size_t slot0 = ((size_t)tile * a.NT + ft) * a.P;
-    constexpr int IT = 16 * 64 / 256;
+    const int first = s_blk0[tile] * 16;  // first row of the tile in its segment
+    // second projection: the tile's real rows; first: every row of its blocks
+    int rows = 16 * s_nblk[tile];
+    if (!UP && s_rows[e] - first < rows) rows = s_rows[e] - first;
+    if (UP) {
+        // item = (row, block of 16 h-columns cb, feature quad fq): a = x.w1 from fragment row
+        // 2cb, b = x.w3 from fragment row 2cb+1, four columns each
+        for (int idx = threadIdx.x; idx < rows * 32; idx += 256) {
+            const int row = idx >> 5, cb = (idx >> 2) & 7, fq = idx & 3;
+            float4 sa = make_float4(0.f, 0.f, 0.f, 0.f), sb = sa;
+            for (int i = 0; i < nb; i++) {
+                if (s_slot[i] < 0) continue;
+                const float* src = a.part + ((size_t)s_slot[i] * (16 * MD_MAX_RB) + row) * 256 + (2 * cb) * 16 + 4 * fq;
+                const float4 va = *(const float4*)src, vb = *(const float4*)(src + 16);
+                sa.x += va.x; sa.y += va.y; sa.z += va.z; sa.w += va.w;
+                sb.x += vb.x; sb.y += vb.y; sb.z += vb.z; sb.w += vb.w;
+            }
+            const float av[4] = {sa.x, sa.y, sa.z, sa.w}, bv[4] = {sb.x, sb.y, sb.z, sb.w};
+            float hv[4];
 #pragma unroll
-    for (int it = 0; it < IT; it++) {
-        const int idx = it * 256 + threadIdx.x;
-        const int r = idx >> 6, c4 = idx & 63;
-        if (r >= nrow) continue;
-        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int p = 0; p < a.P; p++) {
-            const float4 v = *(const float4*)(a.part + ((slot0 + p) * (16 * MD_MAX_RB) + row_lo + r) * 256 + c4 * 4);
-            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            for (int q = 0; q < 4; q++) hv[q] = av[q] / (1.0f + __expf(-av[q])) * bv[q];
+            const int blk = s_blk0[tile] + (row >> 4), t = row & 15;
+            const int colblk = ft * 8 + cb;
+            const int ks_o = colblk >> 1;
+            const int lane_o = ((colblk & 1) * 2 + (fq >> 1)) * 16 + t;
+            uint2 pk;
+            pk.x = moe_pack_bf16x2(hv[0], hv[1]);
+            pk.y = moe_pack_bf16x2(hv[2], hv[3]);
+            *(uint2*)((unsigned char*)a.out +
+                      (((size_t)(s_bbase[e] + blk) * a.KS_out + ks_o) * 64 + lane_o) * 16 +
+                      (fq & 1) * 8) = pk;
         }
-        *(float4*)((float*)a.out + (size_t)(s_row0[e] + first + row_lo + r) * a.C + ft * 256 + c4 * 4) = sum;
+    } else {
+        for (int idx = threadIdx.x; idx < rows * 64; idx += 256) {
+            const int row = idx >> 6, c4 = idx & 63;
+            float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = 0; i < nb; i++) {
+                if (s_slot[i] < 0) continue;
+                const float4 v = *(const float4*)(a.part + ((size_t)s_slot[i] * (16 * MD_MAX_RB) + row) * 256 + c4 * 4);
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+            *(float4*)((float*)a.out + (size_t)(s_row0[e] + first + row) * a.C + ft * 256 + c4 * 4) = sum;
+        }
     }
 }
 
@@ -328,26 +404,20 @@ static inline size_t md_max_blocks(int N, int E) { return (size_t)N / 16 + E; }
 bool moe_ffn_mid_supported(int N, int E, int d, int f) {
     // 16 fragment rows per unit in both projections; reductions in chunks of 4 steps
     if (f % 128 != 0 || d % 256 != 0 || d % (32 * MD_KC) != 0 || f % (32 * MD_KC) != 0) return false;
+    if (moe_num_cus() > MD_MAX_PIECES) return false;
     return (size_t)N / (16 * MD_MAX_RB) + E <= MD_MAX_TILES;
 }
 
 static inline size_t md_max_tiles(int N, int E) { return (size_t)N / (16 * MD_MAX_RB) + E; }
 
-// reduction parts of the second projection: enough for about two units per CU, assuming
-// every expert has one row tile (the host never sees the counts); parts of >= 32 steps
-static int md_down_parts(int E, int d, int f) {
-    int P = 1;
-    const int units1 = E * (d / 256), cus = moe_num_cus();
-    while (P < 8 && units1 * P < 2 * cus && (f / 32) % (2 * P * MD_KC) == 0 && (f / 32) / (2 * P) >= 32)
-        P *= 2;
-    return P;
+// scratch for the pieces of split units: 2 slots of (16*MD_MAX_RB) x 256 fp32 per workgroup
+static inline size_t md_part_bytes() {
+    return (size_t)moe_num_cus() * 2 * (16 * MD_MAX_RB) * 256 * sizeof(float);
 }
 
 size_t moe_ffn_mid_workspace(int N, int E, int d, int f) {
     const size_t nb = md_max_blocks(N, E);
-    const int P = md_down_parts(E, d, f);
-    const size_t part = P > 1 ? md_max_tiles(N, E) * (d / 256) * P * (16 * MD_MAX_RB) * 256 * sizeof(float) : 0;
-    return md_align256(nb * 16 * d * 2) + md_align256(nb * 16 * f * 2) + part;
+    return md_align256(nb * 16 * d * 2) + md_align256(nb * 16 * f * 2) + md_part_bytes();
 }
 
 int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
@@ -376,22 +446,24 @@ int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dty
         hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets,
                            E, N, d, xp);
 
-    const int P = md_down_parts(E, d, f);
+    float* part = (float*)((unsigned char*)ws + md_align256(nb * 16 * d * 2) + md_align256(nb * 16 * f * 2));
+    const unsigned max_units_per_nt = (unsigned)md_max_tiles(N, E);
 
     MidArgs up;
     up.wfrag = (const u32x4_t*)W->w13;
     up.bfrag = xp;
     up.offsets = offsets;
     up.out = hp;
-    up.part = nullptr;
+    up.part = part;
     up.E = E; up.N = N;
     up.KS = d / 32;
     up.FR = 2 * (f / 16);
     up.NT = up.FR / 16;
-    up.P = 1;
     up.KS_out = f / 32;
     up.C = 0;
     hipLaunchKernelGGL(mid_kernel<true>, dim3(grid), dim3(MD_THREADS), lds_bytes, s, up);
+    hipLaunchKernelGGL(mid_fixup_kernel<true>, dim3(max_units_per_nt * up.NT), dim3(256), 0, s, up,
+                       (int)grid);
     moe_record_mid_event(s);
 
     MidArgs dn;
@@ -399,17 +471,15 @@ int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dty
     dn.bfrag = hp;
     dn.offsets = offsets;
     dn.out = yg;
-    dn.part = (float*)((unsigned char*)ws + md_align256(nb * 16 * d * 2) + md_align256(nb * 16 * f * 2));
+    dn.part = part;
     dn.E = E; dn.N = N;
     dn.KS = f / 32;
     dn.FR = d / 16;
     dn.NT = dn.FR / 16;
-    dn.P = P;
     dn.KS_out = 0;
     dn.C = d;
     hipLaunchKernelGGL(mid_kernel<false>, dim3(grid), dim3(MD_THREADS), lds_bytes, s, dn);
-    if (P > 1)
-        hipLaunchKernelGGL(mid_reduce_kernel, dim3((unsigned)(md_max_tiles(N, E) * dn.NT), MD_MAX_RB),
-                           dim3(256), 0, s, dn);
+    hipLaunchKernelGGL(mid_fixup_kernel<false>, dim3(max_units_per_nt * dn.NT), dim3(256), 0, s, dn,
+                       (int)grid);
     return moe_launch_status();
 }
