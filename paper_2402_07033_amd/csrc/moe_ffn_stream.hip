@@ -78,56 +78,89 @@ __device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 
     }
 }
 
+// Row tiles of the routed rows, built by every wave for itself: lane e takes expert e's
+// row range, a wave scan numbers the tiles, and the lane writes its experts' tiles into the
+// wave's own copy of the list in LDS.  No workgroup barrier and no serial walk: the list is
+// ready one global-load latency after the kernel starts.  Returns the number of tiles.
+template <int TR, int MAXT>
+__device__ __forceinline__ int stream_tile_list(const int32_t* offsets, int E, int N, int lane,
+                                                int* te, int* tr0, int* trn) {
+    int lo = 0, hi = 0;
+    if (lane < E) {
+        lo = offsets[lane];
+        hi = offsets[lane + 1];
+    }
+    lo = lo < 0 ? 0 : (lo > N ? N : lo);
+    hi = hi < lo ? lo : (hi > N ? N : hi);
+    const int nt = (hi - lo + TR - 1) / TR;
+    int incl = nt;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const int v = __shfl_up(incl, dlt, 64);
+        if (lane >= dlt) incl += v;
+    }
+    const int first = incl - nt;
+    for (int i = 0; i < nt; i++) {
+        const int ti = first + i;
+        if (ti < MAXT) {
+            const int r = lo + i * TR;
+            te[ti] = lane;
+            tr0[ti] = r;
+            trn[ti] = (hi - r) < TR ? (hi - r) : TR;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int total = __shfl(incl, 63, 64);
+    return __builtin_amdgcn_readfirstlane(total < MAXT ? total : MAXT);
+}
+
 template <int KSW, int NMAT, bool ACT_BF16>
 __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
     constexpr int TERMS = ACT_BF16 ? 1 : 2;
     constexpr int NL = KSW * NMAT;         // fragment loads per unit per wave
     constexpr int R = NL < 16 ? NL : 16;   // loads kept in flight per wave
-    __shared__ int s_te[ST_MAX_TILES], s_tr0[ST_MAX_TILES], s_trn[ST_MAX_TILES];
-    __shared__ int s_nt;
+    __shared__ int s_tiles[ST_MAX_WAVES][3][ST_MAX_TILES];  // per wave: expert, first row, rows
     __shared__ f32x4_t s_red[2][ST_MAX_WAVES][NMAT][64];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    if (a.zero_ptr) {
-        float4* z = (float4*)a.zero_ptr;
-        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (size_t i = (size_t)blockIdx.x * blockDim.x + tid; i < a.zero_n4;
-             i += (size_t)gridDim.x * blockDim.x)
-            z[i] = zero;
-    }
-    __shared__ int s_offs[MOE_MAX_E + 1];
-    if (tid <= a.E) s_offs[tid] = a.offsets[tid];  // one parallel fetch, then a serial walk in LDS
-    __syncthreads();
-    if (tid == 0) {
-        int n = 0;
-        for (int e = 0; e < a.E; e++) {
-            int lo = s_offs[e], hi = s_offs[e + 1];
-            lo = lo < 0 ? 0 : (lo > a.N ? a.N : lo);
-            hi = hi < lo ? lo : (hi > a.N ? a.N : hi);
-            for (int r = lo; r < hi && n < ST_MAX_TILES; r += 16) {
-                s_te[n] = e;
-                s_tr0[n] = r;
-                s_trn[n] = (hi - r) < 16 ? (hi - r) : 16;
-                n++;
-            }
+    // The zero fill of the other projection's output runs last: stores pending next to
+    // loads would turn the waits for the first loads into waits for everything.
+    auto zero_fill = [&]() {
+        if (a.zero_ptr) {
+            float4* z = (float4*)a.zero_ptr;
+            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (size_t i = (size_t)blockIdx.x * blockDim.x + tid; i < a.zero_n4;
+                 i += (size_t)gridDim.x * blockDim.x)
+                z[i] = zero;
         }
-        s_nt = n;
+    };
+    int* s_te = s_tiles[wave][0];
+    int* s_tr0 = s_tiles[wave][1];
+    int* s_trn = s_tiles[wave][2];
+    const int n_tiles =
+        stream_tile_list<16, ST_MAX_TILES>(a.offsets, a.E, a.N, lane, s_te, s_tr0, s_trn);
+    // units of this workgroup: an equal share of tiles x parts x column blocks (the product
+    // stays below 2^31, host check)
+    const unsigned total = (unsigned)n_tiles * (unsigned)a.P * (unsigned)a.NB;
+    const unsigned per = total / gridDim.x, rem = total % gridDim.x;
+    const unsigned u_begin = per * blockIdx.x + rem * blockIdx.x / gridDim.x;
+    const unsigned u_end = per * (blockIdx.x + 1) + rem * (blockIdx.x + 1) / gridDim.x;
+    if (u_begin >= u_end) {  // uniform over the workgroup
+        zero_fill();
+        return;
     }
-    __syncthreads();
-    const long long total = (long long)s_nt * a.P * a.NB;
-    const long long u_begin = total * blockIdx.x / gridDim.x;
-    const long long u_end = total * (blockIdx.x + 1) / gridDim.x;
-    if (u_begin >= u_end) return;  // uniform over the workgroup
 
     const int wave_ks = wave * KSW;  // this wave's first reduction step inside a part
     const int part_ks = a.W * KSW;   // reduction steps per part
     // fragment index of load 0 of unit u for this wave
-    auto frag_base = [&](long long u, int& tile, int& part, int& nb) -> size_t {
-        nb = (int)(u % a.NB);
-        const long long tp = u / a.NB;
-        part = (int)(tp % a.P);
-        tile = (int)(tp / a.P);
+    auto frag_base = [&](unsigned u, int& tile, int& part, int& nb) -> size_t {
+        nb = (int)(u % (unsigned)a.NB);
+        const unsigned tp = u / (unsigned)a.NB;
+        part = (int)(tp % (unsigned)a.P);
+        tile = (int)(tp / (unsigned)a.P);
         const int e = s_te[tile];
         return (((size_t)e * a.NB + nb) * NMAT) * a.KS + (size_t)part * part_ks + wave_ks;
     };
@@ -145,7 +178,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
     bf16x8_t act[KSW][TERMS];
     int cur_tile = -1, cur_part = -1;
     int it = 0;
-    for (long long u = u_begin; u < u_end; ++u, ++it) {
+    for (unsigned u = u_begin; u < u_end; ++u, ++it) {
         const int row0 = s_tr0[tile], rows = s_trn[tile];
         if (tile != cur_tile || part != cur_part) {
             stream_load_act<KSW, ACT_BF16>(act, a.act, a.K, row0, rows, part * part_ks + wave_ks,
@@ -216,6 +249,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
         part = npart;
         nb = nnb;
     }
+    zero_fill();
 }
 
 // Split a reduction of KS steps (of 32) into P parts x W waves x KSW steps.
@@ -286,6 +320,9 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
     int Wu, KSWu, Pu, Wd, KSWd, Pd;
     if (!stream_pick(d / 32, false, Wu, KSWu, Pu) || !stream_pick(f / 32, true, Wd, KSWd, Pd))
         return MOE_ERR_UNSUPPORTED;
+    // unit numbers (tiles x parts x column blocks) are 32-bit in the kernels
+    if ((long long)ST_MAX_TILES * Pd * ((d > f ? d : f) / 16) >= (1ll << 31))
+        return MOE_ERR_UNSUPPORTED;
     float* h = (float*)ws;
     StreamArgs up;
     up.wfrag = (const u32x4_t*)W->w13;
@@ -296,9 +333,8 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
     up.zero_n4 = (size_t)N * d / 4;
     up.E = E; up.N = N; up.K = d; up.C = f;
     up.NB = f / 16; up.KS = d / 32; up.P = 1; up.W = Wu;
-    int rc = (act_dtype == MOE_BF16)
-                 ? stream_dispatch<2, true>(KSWu, Wu, s, up)
-                 : stream_dispatch<2, false>(KSWu, Wu, s, up);
+    int rc = (act_dtype == MOE_BF16) ? stream_dispatch<2, true>(KSWu, Wu, s, up)
+                                     : stream_dispatch<2, false>(KSWu, Wu, s, up);
     if (rc != MOE_OK) return rc;
     moe_record_mid_event(s);
 
