@@ -43,20 +43,25 @@
 #include "moe_frag_pack.h"
 
 // Tile shapes (token blocks of 16 rows x weight fragment rows of 16 features per workgroup;
-// a wave owns all token blocks x FRW = fragment rows / 4; 64 MFMA tiles per wave either way):
+// a wave owns all token blocks x FRW = fragment rows / 4; at most 64 MFMA tiles per wave):
 //   16 x 16 (256 tokens x 256 features): the default;
+//   12 x 16 (192 tokens x 256 features): 97..256 rows per expert on average, where a quarter
+//           of the default tile's matrix work would be padding (measured 2-4 % faster);
 //    8 x 32 (128 tokens x 512 features): experts with up to ~128 rows, where the default
 //           tile is half empty -- twice the weight bytes per step, no padded matrix work.
 #define GG_THREADS 256
 #define GG_NS 8            // LDS stages of B fragments (one KiB per token block each)
 // The weight fragments of step k are requested GG_LA steps earlier into a register ring that
 // is named statically, so the step loop is unrolled GG_U times (GG_LA < GG_U, reduction %
-// GG_U == 0; GG_LA <= GG_NS - 3, see the waits in the step).  A deeper ring (8 / 5) measured
-// no faster.
+// GG_U == 0; GG_LA <= GG_NS - 3, see the waits in the step).  Deeper rings (8 / 5 with 8
+// stages, 8 / 7 with 10 stages on the 192-row tile) measured no faster.
 #define GG_U 4
 #define GG_LA 3
 #ifndef GG_WIDE_MAX_ROWS
 #define GG_WIDE_MAX_ROWS 96  // mean rows per expert up to which the 128 x 512 tile is used
+#endif
+#ifndef GG_R192_MAX_ROWS
+#define GG_R192_MAX_ROWS 256  // ... and up to which the 192 x 256 tile is used
 #endif
 
 // ------------------------------------------------------------------- GEMM ----
@@ -139,15 +144,17 @@ __device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offse
 
 // Cut points of the left-over tiles' joint reduction (S = R tiles x KS steps) for the
 // workgroups of one XCD: workgroup j covers [cut(j), cut(j+1)).  Pieces are multiples of
-// `unit` steps (KS is one too) and no piece is shorter than 8 steps.
-__device__ __forceinline__ int gg_piece_cut(int j, int S, int KS, int wgs, int unit) {
+// `unit` steps (KS is one too) and no piece is shorter than the smallest multiple of `unit`
+// that covers the `ns` LDS stages of the kernel's pipeline.
+__device__ __forceinline__ int gg_piece_cut(int j, int S, int KS, int wgs, int unit, int ns) {
+    const int minp = (ns + unit - 1) / unit * unit;
     int per = ((S + wgs - 1) / wgs + unit - 1) / unit * unit;
     per = per < 32 ? 32 : per;
     const int c = j * per;
     if (c >= S) return S;
     const int r = c % KS;
-    if (r < 8) return c - r;
-    if (KS - r < 8) return c + (KS - r);
+    if (r < minp) return c - r;
+    if (KS - r < minp) return c + (KS - r);
     return c;
 }
 
@@ -185,15 +192,15 @@ __device__ __forceinline__ void gg_tile_src(const GroupedArgs& a, const TileInfo
 // takes two launches, because an epilogue with both the SiLU*mul body and the raw store of
 // partial sums makes the compiler spill ~150 accumulators per tile).
 // NBW x FRW: token blocks of the tile x fragment rows of a wave (16 x 4 or 8 x 8).
-template <bool UP, int NBW, int FRW, int MODE>
+template <bool UP, int NBW, int FRW, int MODE, int U, int LA, int NS>
 __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
-    static_assert(NBW * FRW == 64 && NBW % 4 == 0, "64 MFMA tiles per wave");
-    constexpr int U = GG_U, LA = GG_LA;
+    static_assert(NBW * FRW <= 64 && NBW % 4 == 0, "at most 64 MFMA tiles (256 accumulators) per wave");
+    static_assert(LA < U && LA <= NS - 3, "ring and stage depths, see the waits in the step");
     constexpr int FROWS = 4 * FRW;     // fragment rows of the workgroup tile
     constexpr int NBQ = NBW / 4;       // token blocks each wave requests into LDS per step
     constexpr int VREQ = FRW + NBQ;    // vector-memory requests per wave and step
     extern __shared__ __align__(16) unsigned char smem[];
-    u32x4_t* lds = (u32x4_t*)smem;  // [GG_NS stages][NBW fragments][64 lanes]
+    u32x4_t* lds = (u32x4_t*)smem;  // [NS stages][NBW fragments][64 lanes]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // fragment rows [FRW*wave, +FRW)
@@ -220,7 +227,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     if (split) {
         const int R = chunk - n_full * wgs;
         const int S = R * a.KS;
-        const int c0 = gg_piece_cut(me, S, a.KS, wgs, U), c1 = gg_piece_cut(me + 1, S, a.KS, wgs, U);
+        const int c0 = gg_piece_cut(me, S, a.KS, wgs, U, NS), c1 = gg_piece_cut(me + 1, S, a.KS, wgs, U, NS);
         if (c0 < c1) {
             const int rA = c0 / a.KS;
             const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
@@ -258,7 +265,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     TileSrc<FRW, NBQ> scur, snxt;
     gg_tile_src(a, cur, wave, scur);
     if (has_next) gg_tile_src(a, nxt, wave, snxt); else snxt = scur;
-    int KT = cur.klen;  // steps of the current unit: a multiple of 4, >= GG_NS
+    int KT = cur.klen;  // steps of the current unit: a multiple of U, >= NS
 
     // look-ahead sources: reduction step j of the current tile, or j-KT of the next one
     auto b_src = [&](int i, int j) -> const char* {
@@ -269,11 +276,11 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         const u32x4_t* p = (j < KT) ? scur.a[jr] + (size_t)j * 64 : snxt.a[jr] + (size_t)(j - KT) * 64;
         return (const u32x4_t*)((const char*)p + voff);
     };
-    // g = running step count of this workgroup (never reset): LDS stage g % GG_NS
+    // g = running step count of this workgroup (never reset): LDS stage g % NS
     auto issue_b = [&](int i, int j, int gstage) {
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void*)b_src(i, j),
-            (__attribute__((address_space(3))) void*)(lds + ((gstage % GG_NS) * NBW + NBQ * wave + i) * 64),
+            (__attribute__((address_space(3))) void*)(lds + ((gstage % NS) * NBW + NBQ * wave + i) * 64),
             16, 0, 0);
     };
 
@@ -282,7 +289,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
     bf16x8_t breg[NBW];
 
     // ---- prologue of the first tile: request stages 0..NS-2 and A of steps 0..PA-2 ----
-    for (int j = 0; j < GG_NS - 1; j++)
+    for (int j = 0; j < NS - 1; j++)
 #pragma unroll
         for (int i = 0; i < NBQ; i++) issue_b(i, j, j);
 #pragma unroll
@@ -309,13 +316,13 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
         // the current tile, so there is nothing to decide (compile-time after inlining).
         auto step = [&](int k, u32x4_t(&Ac)[FRW], u32x4_t(&An)[FRW], const bool fast) {
             // do the look-ahead requests exist (in this tile or the next one)?
-            const bool la_b = fast || has_next || (k + GG_NS - 1 < KT);
+            const bool la_b = fast || has_next || (k + NS - 1 < KT);
             const bool la_a = fast || has_next || (k + LA < KT);
             const bool more = fast || has_next || (k + 1 < KT);
             // The weights of step k were requested LA steps ago, after that step's requests
-            // for stage k+GG_NS-1-LA; requests retire in order, so with at most the last
+            // for stage k+NS-1-LA; requests retire in order, so with at most the last
             // LA-1 steps' worth still in flight they have arrived, and so have the stages
-            // requested before them (LA <= GG_NS-3: up to stage k+2).  Once the stream has
+            // requested before them (LA <= NS-3: up to stage k+2).  Once the stream has
             // ended (last tile, no look-ahead) wait for everything.
             if (la_b) GG_WAIT_VMCNT((LA - 1) * VREQ);
             else GG_WAIT_VMCNT(0);
@@ -324,20 +331,20 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             // buffers refilled during steps k and k+1 (stages k-1 and k) were last read
             // before this barrier.
             if (more && (k & 1) == 0) __builtin_amdgcn_s_barrier();
-            const u32x4_t* pb = lds + ((g + 1) % GG_NS) * NBW * 64 + lane;
-            // request number v of this step: 0..NBQ-1 = this wave's blocks of stage k+GG_NS-1
+            const u32x4_t* pb = lds + ((g + 1) % NS) * NBW * 64 + lane;
+            // request number v of this step: 0..NBQ-1 = this wave's blocks of stage k+NS-1
             // (straight into LDS), NBQ.. = its FRW weight fragments of step k+LA
             auto issue = [&](const int v) {
                     if (v < NBQ) {
                         if (fast) {
                             __builtin_amdgcn_global_load_lds(
                                 (const __attribute__((address_space(1))) void*)(
-                                    (const char*)(scur.b[v] + (size_t)(k + GG_NS - 1) * 64) + voff),
+                                    (const char*)(scur.b[v] + (size_t)(k + NS - 1) * 64) + voff),
                                 (__attribute__((address_space(3))) void*)(
-                                    lds + (((g + GG_NS - 1) % GG_NS) * NBW + NBQ * wave + v) * 64),
+                                    lds + (((g + NS - 1) % NS) * NBW + NBQ * wave + v) * 64),
                                 16, 0, 0);
                         } else if (la_b) {
-                            issue_b(v, k + GG_NS - 1, g + GG_NS - 1);
+                            issue_b(v, k + NS - 1, g + NS - 1);
                         }
                     } else {
                         if (fast)
@@ -364,8 +371,8 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
             }
             g++;
         };
-        // steps whose look-aheads (k+GG_NS-1 at most) stay inside this tile: no conditions
-        const int k_fast = ((KT - GG_NS + 1) / U) * U;
+        // steps whose look-aheads (k+NS-1 at most) stay inside this tile: no conditions
+        const int k_fast = ((KT - NS + 1) / U) * U;
         int k = 0;
         for (; k < k_fast; k += U) {
 #pragma unroll
@@ -457,7 +464,7 @@ __global__ __launch_bounds__(GG_THREADS) void gg_gemm_kernel(GroupedArgs a) {
 // FROWS = fragment rows of the tile shape (16 or 32); a.TB = its token blocks.
 #define GG_FIX_ROWS 16
 template <bool UP, int FROWS>
-__global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, int unit) {
+__global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, int unit, int ns) {
     __shared__ int s_slot[64];
     __shared__ int s_n;
     constexpr int RS = 16 * FROWS;  // floats per row of a partial tile
@@ -487,7 +494,8 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
         const int S = R * a.KS;
         int slot = -1;
         if (j < wgs) {
-            const int c0 = gg_piece_cut(j, S, a.KS, wgs, unit), c1 = gg_piece_cut(j + 1, S, a.KS, wgs, unit);
+            const int c0 = gg_piece_cut(j, S, a.KS, wgs, unit, ns),
+                      c1 = gg_piece_cut(j + 1, S, a.KS, wgs, unit, ns);
             if (c0 < c1) {
                 const int rA = c0 / a.KS;
                 const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
@@ -604,13 +612,61 @@ size_t moe_ffn_grouped_workspace(int N, int E, int d, int f) {
     return gg_align256(nb * 16 * d * 2) + gg_align256(nb * 16 * f * 2) + gg_part_bytes();
 }
 
-// Kernel variants by rows per expert (see the tile shapes at the top of the file).
-enum GgVariant { GG_STD = 0, GG_WIDE = 1 };
+// Kernel variants by rows per expert (see the tile shapes at the top of the file): token
+// blocks and fragment rows of the tile, unroll / weight look-ahead / LDS stages of the loop.
+enum GgVariant { GG_STD = 0, GG_WIDE = 1, GG_R192 = 2, GG_NVARIANTS = 3 };
+struct GgShape { int tb, frows, u, la, ns; };
+static GgShape gg_shape(GgVariant v) {
+    switch (v) {
+        case GG_WIDE: return {8, 32, GG_U, GG_LA, GG_NS};
+        case GG_R192: return {12, 16, GG_U, GG_LA, GG_NS};
+        default: return {16, 16, GG_U, GG_LA, GG_NS};
+    }
+}
 
 template <bool UP, int MODE>
 static const void* gg_kernel_ptr(GgVariant v) {
-    return v == GG_WIDE ? (const void*)gg_gemm_kernel<UP, 8, 8, MODE>
-                        : (const void*)gg_gemm_kernel<UP, 16, 4, MODE>;
+    switch (v) {
+        case GG_WIDE: return (const void*)gg_gemm_kernel<UP, 8, 8, MODE, GG_U, GG_LA, GG_NS>;
+        case GG_R192: return (const void*)gg_gemm_kernel<UP, 12, 4, MODE, GG_U, GG_LA, GG_NS>;
+        default: return (const void*)gg_gemm_kernel<UP, 16, 4, MODE, GG_U, GG_LA, GG_NS>;
+    }
+}
+
+// One projection: the persistent GEMM (whole tiles; for the first projection the pieces of
+// the left-over tiles are a second launch) and the fix-up of the pieces.
+template <bool UP>
+static int gg_launch_projection(GroupedArgs& a, GgVariant v, unsigned pgrid, hipStream_t s) {
+    const GgShape sh = gg_shape(v);
+    a.TB = sh.tb;
+    a.FROWS = sh.frows;
+    if (a.FR % a.FROWS != 0) return MOE_ERR_UNSUPPORTED;
+    a.NT = a.FR / a.FROWS;
+    // pieces of >= 32 steps go to scratch and a fix-up kernel adds them; it lists the pieces
+    // of a tile with one wave, hence at most 64 workgroups per XCD
+    a.split = (a.KS >= 64 && pgrid / 8 <= 64) ? 1 : 0;
+    void* params[1] = {(void*)&a};
+    const size_t lds_bytes = (size_t)sh.ns * a.TB * MOE_FRAG_BYTES;
+    if (UP) {
+        MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 1>(v), dim3(pgrid), dim3(GG_THREADS), params,
+                                    lds_bytes, s));
+        if (a.split)
+            MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 2>(v), dim3(pgrid), dim3(GG_THREADS),
+                                        params, lds_bytes, s));
+    } else {
+        MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<false, 0>(v), dim3(pgrid), dim3(GG_THREADS), params,
+                                    lds_bytes, s));
+    }
+    if (a.split) {
+        const dim3 fgrid(pgrid, (unsigned)a.TB);
+        if (a.FROWS == 32)
+            hipLaunchKernelGGL((gg_fixup_kernel<UP, 32>), fgrid, dim3(256), 0, s, a, (int)(pgrid / 8),
+                               sh.u, sh.ns);
+        else
+            hipLaunchKernelGGL((gg_fixup_kernel<UP, 16>), fgrid, dim3(256), 0, s, a, (int)(pgrid / 8),
+                               sh.u, sh.ns);
+    }
+    return MOE_OK;
 }
 
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
@@ -620,32 +676,41 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     // down tile = 256 features: d % 256 == 0; both give reductions of >= 8 steps, step
     // counts that are multiples of 4.
     if (f % 128 != 0 || d % 256 != 0) return MOE_ERR_UNSUPPORTED;
-    // the step loop is unrolled GG_U times and looks GG_NS-1 steps ahead
-    if ((d / 32) % GG_U != 0 || (f / 32) % GG_U != 0 || d / 32 < GG_NS || f / 32 < GG_NS)
-        return MOE_ERR_UNSUPPORTED;
     // Variant by the mean number of rows per expert (the host never sees the real counts):
     // up to GG_WIDE_MAX_ROWS the 128-token x 512-feature tile (needs f % 256 == 0 for the
-    // first projection, d % 512 == 0 for the second; each falls back on its own).
+    // first projection, d % 512 == 0 for the second; each falls back on its own), up to
+    // GG_R192_MAX_ROWS the 192-token x 256-feature one, above that 256 x 256.
     const long long mean_rows = ((long long)N + E - 1) / E;
     GgVariant vu = GG_STD, vd = GG_STD;
     if (mean_rows <= GG_WIDE_MAX_ROWS) {
         if (f % 256 == 0) vu = GG_WIDE;
         if (d % 512 == 0) vd = GG_WIDE;
+    } else if (mean_rows <= GG_R192_MAX_ROWS) {
+        vu = vd = GG_R192;
     }
+    // the step loop is unrolled u times and looks ns-1 steps ahead: a variant whose loop does
+    // not fit a reduction gives way to the standard one
+    auto fits = [&](GgVariant v, int ks) {
+        const GgShape sh = gg_shape(v);
+        return ks % sh.u == 0 && ks >= sh.ns;
+    };
+    if (!fits(vu, d / 32)) vu = GG_STD;
+    if (!fits(vd, f / 32)) vd = GG_STD;
+    if (!fits(vu, d / 32) || !fits(vd, f / 32)) return MOE_ERR_UNSUPPORTED;
     const size_t nb = gg_max_blocks(N, E);
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
-    const size_t lds_max = GG_NS * 16 * MOE_FRAG_BYTES;
     const unsigned pgrid = (unsigned)((moe_num_cus() + 7) / 8 * 8);  // persistent: one per CU
 
     static bool attr_set = false;
     if (!attr_set) {
-        for (int v = 0; v < 2; v++) {
+        for (int v = 0; v < GG_NVARIANTS; v++) {
+            const GgShape sh = gg_shape((GgVariant)v);
             const void* all[3] = {gg_kernel_ptr<true, 1>((GgVariant)v), gg_kernel_ptr<true, 2>((GgVariant)v),
                                   gg_kernel_ptr<false, 0>((GgVariant)v)};
             for (int i = 0; i < 3; i++)
                 MOE_HIP_TRY(hipFuncSetAttribute(all[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                (int)lds_max));
+                                                (int)((size_t)sh.ns * sh.tb * MOE_FRAG_BYTES)));
         }
         attr_set = true;
     }
@@ -657,10 +722,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
         hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets,
                            E, N, d, xp);
 
-    // Left-over tiles of each XCD (tile count not a multiple of the workgroup count) are cut
-    // along the reduction; pieces of >= 32 steps go to scratch behind hp and a fix-up kernel
-    // adds them (and applies SiLU*mul for the first projection).  The fix-up lists the
-    // pieces of a tile with one wave, hence at most 64 workgroups per XCD.
+    // scratch of the pieces of left-over tiles, behind the two fragment buffers
     float* part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +
                            gg_align256(nb * 16 * f * 2));
 
@@ -672,31 +734,11 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     up.E = E; up.N = N;
     up.KS = d / 32;
     up.FR = 2 * (f / 16);
-    up.TB = vu == GG_WIDE ? 8 : 16;
-    up.FROWS = vu == GG_WIDE ? 32 : 16;
-    up.NT = up.FR / up.FROWS;
     up.KS_out = f / 32;
     up.C = 0;
-    up.split = (d / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;
     up.part = part;
-    {
-        void* params[1] = {(void*)&up};
-        const size_t lds_bytes = (size_t)GG_NS * up.TB * MOE_FRAG_BYTES;
-        const int unit = GG_U;
-        MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 1>(vu), dim3(pgrid), dim3(GG_THREADS), params,
-                                    lds_bytes, s));
-        if (up.split) {
-            MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<true, 2>(vu), dim3(pgrid), dim3(GG_THREADS),
-                                        params, lds_bytes, s));
-            const dim3 fgrid(pgrid, (unsigned)up.TB);
-            if (vu == GG_WIDE)
-                hipLaunchKernelGGL((gg_fixup_kernel<true, 32>), fgrid, dim3(256), 0, s, up,
-                                   (int)(pgrid / 8), unit);
-            else
-                hipLaunchKernelGGL((gg_fixup_kernel<true, 16>), fgrid, dim3(256), 0, s, up,
-                                   (int)(pgrid / 8), unit);
-        }
-    }
+    int rc = gg_launch_projection<true>(up, vu, pgrid, s);
+    if (rc != MOE_OK) return rc;
     moe_record_mid_event(s);
 
     GroupedArgs dn;
@@ -707,28 +749,10 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     dn.E = E; dn.N = N;
     dn.KS = f / 32;
     dn.FR = d / 16;
-    dn.TB = vd == GG_WIDE ? 8 : 16;
-    dn.FROWS = vd == GG_WIDE ? 32 : 16;
-    dn.NT = dn.FR / dn.FROWS;
     dn.KS_out = 0;
     dn.C = d;
-    dn.split = (f / 32 >= 64 && pgrid / 8 <= 64) ? 1 : 0;
     dn.part = part;
-    {
-        void* params[1] = {(void*)&dn};
-        const size_t lds_bytes = (size_t)GG_NS * dn.TB * MOE_FRAG_BYTES;
-        const int unit = GG_U;
-        MOE_HIP_TRY(hipLaunchKernel(gg_kernel_ptr<false, 0>(vd), dim3(pgrid), dim3(GG_THREADS), params,
-                                    lds_bytes, s));
-        if (dn.split) {
-            const dim3 fgrid(pgrid, (unsigned)dn.TB);
-            if (vd == GG_WIDE)
-                hipLaunchKernelGGL((gg_fixup_kernel<false, 32>), fgrid, dim3(256), 0, s, dn,
-                                   (int)(pgrid / 8), unit);
-            else
-                hipLaunchKernelGGL((gg_fixup_kernel<false, 16>), fgrid, dim3(256), 0, s, dn,
-                                   (int)(pgrid / 8), unit);
-        }
-    }
+    rc = gg_launch_projection<false>(dn, vd, pgrid, s);
+    if (rc != MOE_OK) return rc;
     return moe_launch_status();
 }

@@ -161,14 +161,18 @@ def test_layer_bf16_stream_path(moe, T, d, f, E, k, xdt):
 @pytest.mark.parametrize("T,d,f,E,k,xdt", [
     (1, 256, 512, 8, 2, mi.F32), (100, 256, 512, 8, 2, mi.BF16), (600, 256, 384, 4, 2, mi.BF16),
     (300, 512, 1024, 8, 2, mi.F32), (1100, 256, 256, 3, 1, mi.BF16),
-    # few rows per expert: the deep-ring variant that skips empty row quarters; f = 384 keeps
-    # the second projection on the default variant, f = 2304 cuts its tiles along the reduction
+    # few rows per expert (tiles mostly padding); f = 2304 cuts left-over tiles along the
+    # reduction
     (70, 256, 384, 8, 2, mi.F32), (150, 512, 2304, 8, 2, mi.BF16), (9, 256, 2048, 16, 2, mi.BF16),
     # 41..96 rows per expert: the 128-token x 512-feature tile (first projection needs
     # f % 256 == 0, second d % 512 == 0, else that projection keeps the default tile);
     # d = 2048 / f = 2304 also cut left-over tiles along the reduction
     (380, 1024, 2304, 8, 2, mi.BF16), (300, 256, 512, 8, 2, mi.F32), (330, 512, 384, 4, 1, mi.BF16),
-    (370, 2048, 512, 8, 2, mi.BF16)])
+    (370, 2048, 512, 8, 2, mi.BF16),
+    # 97..256 rows per expert: the 192-token x 256-feature tile (hot experts span several
+    # tiles, the last one ragged); f = 2304 / d = 2048 cut left-over tiles along the reduction
+    (500, 512, 1024, 8, 2, mi.BF16), (900, 1024, 2304, 8, 2, mi.BF16), (1000, 256, 384, 8, 2, mi.F32),
+    (460, 2048, 512, 4, 1, mi.BF16)])
 def test_layer_bf16_grouped_path(moe, T, d, f, E, k, xdt):
     cfg = mi.small_config("gg", T, d, f, E, k, 600 + T + d, w_dtype=mi.BF16, x_dtype=xdt,
                           zipf_s=1.2)
