@@ -327,7 +327,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=None,
-                    help="override T of a single-layer workload (sweeps; the JSON names it)")
+                    help="override T of the workload (sweeps; the JSON names it)")
     ap.add_argument("--ffn-path", default="auto", choices=["auto", "stream", "grouped", "mid"],
                     help="force the expert-FFN kernel family (sweeps)")
     ap.add_argument("--fused-gate", action="store_true",
@@ -356,7 +356,7 @@ def main():
     wl = dict(WORKLOADS[args.workload])
     global D, F, E, K
     D, F, E, K = wl.get("shape", (D, F, E, K))
-    if args.tokens is not None and "layers" not in wl:
+    if args.tokens is not None:
         wl["T"] = args.tokens
     T = wl["T"]
     if "layers" in wl:
