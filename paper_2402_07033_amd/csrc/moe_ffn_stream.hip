@@ -255,8 +255,8 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
 // Split a reduction of KS steps (of 32) into P parts x W waves x KSW steps.
 static bool stream_pick(int KS, bool allow_parts, int& W, int& KSW, int& P) {
     int best = -1;
-    const int ksws[5] = {16, 8, 4, 2, 1};
-    for (int i = 0; i < 5; i++)
+    const int ksws[6] = {16, 10, 8, 4, 2, 1};
+    for (int i = 0; i < 6; i++)
         for (int w = ST_MAX_WAVES; w >= 1; w--) {
             const int span = w * ksws[i];
             if (KS % span) continue;
@@ -297,9 +297,10 @@ static int stream_dispatch(int KSW, int waves, hipStream_t s, const StreamArgs& 
         case 4: fn = (const void*)stream_kernel<4, NMAT, ACT_BF16>; slot = 2; break;
         case 8: fn = (const void*)stream_kernel<8, NMAT, ACT_BF16>; slot = 3; break;
         case 16: fn = (const void*)stream_kernel<16, NMAT, ACT_BF16>; slot = 4; break;
+        case 10: fn = (const void*)stream_kernel<10, NMAT, ACT_BF16>; slot = 5; break;
         default: return MOE_ERR_UNSUPPORTED;
     }
-    static int occ_cache[5][ST_MAX_WAVES + 1];  // per instantiation: 0 = not asked yet
+    static int occ_cache[6][ST_MAX_WAVES + 1];  // per instantiation: 0 = not asked yet
     int occ = occ_cache[slot][waves];
     if (occ == 0) {
         MOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, 64 * waves, 0));

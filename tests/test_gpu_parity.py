@@ -149,7 +149,9 @@ def test_layer_fp32_shapes(moe, T, d, f, E, k):
 @pytest.mark.parametrize("T,d,f,E,k,xdt", [
     (1, 256, 512, 8, 2, mi.F32), (16, 256, 512, 8, 2, mi.F32), (16, 512, 1024, 8, 2, mi.BF16),
     (7, 1024, 1792, 4, 2, mi.F32), (40, 256, 512, 8, 1, mi.F32), (3, 2048, 3584, 8, 2, mi.F32),
-    (16, 128, 256, 3, 3, mi.F32)])
+    (16, 128, 256, 3, 3, mi.F32),
+    # reductions of 10 steps per wave (f / 32 = 20 and 50; d / 32 = 10 for the first projection)
+    (5, 320, 640, 4, 2, mi.F32), (2, 256, 1600, 8, 2, mi.BF16)])
 def test_layer_bf16_stream_path(moe, T, d, f, E, k, xdt):
     cfg = mi.small_config("st", T, d, f, E, k, 500 + T + d, w_dtype=mi.BF16, x_dtype=xdt,
                           zipf_s=1.2)
