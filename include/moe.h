@@ -45,12 +45,12 @@ typedef enum {
 } moe_status_t;
 
 /* Which expert-FFN kernels to run.  AUTO picks from N, E and the shape: STREAM up to 72 routed
- * rows, MID up to 40 rows per expert on average, GROUPED above. */
+ * rows, MID up to 10 rows per expert on average, GROUPED above. */
 typedef enum {
     MOE_FFN_AUTO = 0,
     MOE_FFN_STREAM = 1, /* decode: weight-streaming MFMA kernels, <=16 rows per pass */
     MOE_FFN_GROUPED = 2, /* prefill: grouped LDS-tiled MFMA GEMM */
-    MOE_FFN_MID = 3      /* tens of rows per expert: weight-streaming grouped GEMM, rows via LDS */
+    MOE_FFN_MID = 3      /* a handful of rows for each of many experts: weight-streaming grouped GEMM */
 } moe_ffn_path_t;
 
 typedef struct moe_weights moe_weights_t; /* opaque, library-owned */

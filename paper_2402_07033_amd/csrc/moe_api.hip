@@ -4,7 +4,7 @@
 
 // mean rows per expert up to which AUTO takes the weight-streaming grouped GEMM
 #ifndef MOE_MID_MAX_ROWS
-#define MOE_MID_MAX_ROWS 40
+#define MOE_MID_MAX_ROWS 10
 #endif
 
 static inline bool dims_ok(int d) { return d >= 64 && d % 64 == 0 && d <= (1 << 20); }
@@ -111,12 +111,14 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
         return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
     }
     if (path == MOE_FFN_AUTO) {
-        // Measured crossovers (Mixtral shape, Zipf-skewed routing):
+        // Measured crossovers (Mixtral shape and the 16-expert shape, Zipf-skewed routing; with
+        // balanced routing each kernel stays ahead somewhat longer than its limit here):
         //   up to 72 routed rows the decode kernels, which stream each active expert once
-        //   per 16-row tile at ~6 TB/s;
+        //   per 16-row tile at ~6.5 TB/s;
         //   up to MOE_MID_MAX_ROWS rows per expert on average the weight-streaming grouped
-        //   GEMM (every expert's matrices are read about once, many row blocks per read);
-        //   above that the LDS-tiled grouped GEMM.
+        //   GEMM (many experts with a handful of rows each: 11 % ahead at 6 rows per expert,
+        //   5 % behind at 12);
+        //   above that the LDS-tiled grouped GEMM, whose smaller tiles stream the weights too.
         if (N <= 72 && moe_ffn_stream_supported(W->d, W->f))
             path = MOE_FFN_STREAM;
         else if ((long long)N <= (long long)MOE_MID_MAX_ROWS * W->E &&

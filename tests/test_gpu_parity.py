@@ -259,9 +259,10 @@ def test_single_expert_layer_and_auto_threshold(moe):
     cfg = mi.small_config("E1", 9, 256, 512, 1, 1, 77, w_dtype=mi.BF16)
     _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16)
     # AUTO on either side of its switches: decode kernels up to 72 routed rows, the
-    # weight-streaming grouped GEMM up to 40 rows per expert (320 rows here), then the
-    # LDS-tiled grouped GEMM (128 x 512 tile up to 96 rows per expert, 256 x 256 above)
-    for T in (36, 37, 160, 161, 384, 385):
+    # weight-streaming grouped GEMM up to 10 rows per expert (80 rows here), then the
+    # LDS-tiled grouped GEMM (128 x 512 tile up to 96 rows per expert, 192 x 256 up to 256,
+    # 256 x 256 above)
+    for T in (36, 37, 40, 41, 384, 385, 1024, 1025):
         cfg = mi.small_config("thr", T, 256, 512, 8, 2, 80 + T, w_dtype=mi.BF16, zipf_s=1.2)
         _layer_parity(moe, cfg, mi.make_layer(cfg, threads=1), TOL_BF16)
 
