@@ -318,6 +318,37 @@ def mfma_ceiling(torch, moe):
     return res
 
 
+def hbm_ceiling(torch, moe):
+    """Rate of a plain streaming read on this board (one launch per measurement over buffers
+    that are rotated so that no launch finds its data in the last-level cache): context for
+    the HBM roofline.  Sizes: the first and second projection's bytes at T=1, and 1 GiB."""
+    events = HipEvents()
+    stream = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    res = {}
+    for name, nbytes in (("224MiB", 224 << 20), ("448MiB", 448 << 20), ("1GiB", 1 << 30)):
+        nbuf = max(3, (3 << 30) // nbytes)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(5)
+        bufs = [torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device="cuda",
+                              generator=g) for _ in range(nbuf)]
+        for b in bufs[:2]:
+            moe.moe_hbm_read_probe(b, sink)
+        torch.cuda.synchronize()
+        reps = 4 * nbuf
+        e0, e1 = events.create(), events.create()
+        events.record(e0, stream)
+        read = 0
+        for r in range(reps):
+            read += moe.moe_hbm_read_probe(bufs[r % nbuf], sink)
+        events.record(e1, stream)
+        ms = events.elapsed_ms(e0, e1)
+        res[name] = {"us_per_launch": ms * 1e3 / reps, "GBs": read / (ms * 1e-3) / 1e9}
+        del bufs
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -335,6 +366,8 @@ def main():
                          "of moe_route + moe_permute (same outputs)")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="only measure the sustained matrix-core rate of this board")
+    ap.add_argument("--hbm-ceiling", action="store_true",
+                    help="only measure what a plain streaming read gets from HBM on this board")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size reference dispatch "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -352,6 +385,10 @@ def main():
     if args.mfma_ceiling:
         print(json.dumps({"mfma_sustained_TFLOPs_bf16_16x16x32": mfma_ceiling(torch, moe),
                           "published_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS}))
+        return
+    if args.hbm_ceiling:
+        print(json.dumps({"hbm_streaming_read": hbm_ceiling(torch, moe),
+                          "published_peak_GBs": HBM_PEAK_GBS}))
         return
     wl = dict(WORKLOADS[args.workload])
     global D, F, E, K

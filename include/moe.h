@@ -227,6 +227,17 @@ int moe_set_ffn_mid_event(void* hip_event);
 int moe_mfma_rate_probe(const void* operands, int iters, float* out, double* flops,
                         void* stream);
 
+/* Measurement probe: one launch of a plain streaming-read kernel (one workgroup of 8 waves
+ * per CU, contiguous shares, 16 one-KiB non-temporal requests in flight per wave) - the
+ * request structure of the decode kernels without set-up, arithmetic or epilogue; context for
+ * the HBM roofline (what fraction of the published 8 TB/s a pure read reaches on this board).
+ *   data   buffer to read (DEVICE), 16-byte aligned
+ *   bytes  its size; reads floor(bytes / (CUs * 8 * 16 KiB)) * 16 KiB per wave (at least
+ *          16 KiB per wave, else MOE_ERR_INVALID_ARG), so slightly less than `bytes`
+ *   sink   4 bytes (DEVICE) that keep the loads alive
+ */
+int moe_hbm_read_probe(const void* data, size_t bytes, unsigned* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -6,7 +6,7 @@ memory and streams.  There is no CPU fallback: importing the binding's
 functions without the built library raises.
 """
 from .binding import (StackBuffers, moe_route_permute, moe_norm_route_permute,
-                      moe_combine_residual, moe_combine_norm_route_permute, moe_mfma_rate_probe, moe_stack_forward, MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID, MOE_FFN_STREAM,
+                      moe_combine_residual, moe_combine_norm_route_permute, moe_mfma_rate_probe, moe_hbm_read_probe, moe_stack_forward, MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID, MOE_FFN_STREAM,
                       MoeError, PackedWeights, lib, lib_path, moe_combine, moe_expert_ffn,
                       moe_expert_ffn_workspace, moe_layer, moe_permute, moe_residual_add,
                       moe_rmsnorm, moe_rmsnorm_router_logits, moe_route, moe_router_logits, moe_set_ffn_mid_event,
@@ -16,6 +16,7 @@ from .binding import (StackBuffers, moe_route_permute, moe_norm_route_permute,
 __all__ = [
     "StackBuffers", "moe_stack_forward", "moe_route_permute", "moe_norm_route_permute",
     "moe_combine_residual", "moe_combine_norm_route_permute", "moe_mfma_rate_probe",
+    "moe_hbm_read_probe",
     "MOE_BF16", "MOE_F32", "MOE_FFN_AUTO", "MOE_FFN_GROUPED", "MOE_FFN_MID", "MOE_FFN_STREAM", "MoeError",
     "PackedWeights", "lib", "lib_path", "moe_combine", "moe_expert_ffn",
     "moe_expert_ffn_workspace", "moe_layer", "moe_permute", "moe_residual_add", "moe_rmsnorm",

@@ -20,8 +20,8 @@ EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
            "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
-           "moe_mfma_rate_probe", "moe_route_permute", "moe_norm_route_permute",
-           "moe_combine_residual", "moe_combine_norm_route_permute",
+           "moe_mfma_rate_probe", "moe_hbm_read_probe", "moe_route_permute",
+           "moe_norm_route_permute", "moe_combine_residual", "moe_combine_norm_route_permute",
            "moe_rmsnorm_router_logits")
 
 
@@ -67,6 +67,8 @@ def lib():
         L.moe_set_ffn_mid_event.restype = C.c_int
         L.moe_mfma_rate_probe.argtypes = [vp, i32, vp, C.POINTER(C.c_double), vp]
         L.moe_mfma_rate_probe.restype = C.c_int
+        L.moe_hbm_read_probe.argtypes = [vp, C.c_size_t, vp, vp]
+        L.moe_hbm_read_probe.restype = C.c_int
         L.moe_route_permute.argtypes = [vp, i32, i32, i32, vp, i32] + [vp] * 8
         L.moe_route_permute.restype = C.c_int
         L.moe_norm_route_permute.argtypes = [vp, vp, i32, i32, i32, i32, f32] + [vp] * 10
@@ -79,8 +81,8 @@ def lib():
         for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
                   "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
                   "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
-           "moe_mfma_rate_probe", "moe_route_permute", "moe_norm_route_permute",
-           "moe_combine_residual"):
+                  "moe_mfma_rate_probe", "moe_hbm_read_probe", "moe_route_permute",
+                  "moe_norm_route_permute", "moe_combine_residual"):
             getattr(L, n).restype = C.c_int
         _lib = L
     return _lib
@@ -292,6 +294,16 @@ def moe_mfma_rate_probe(operands: torch.Tensor, iters: int, out: torch.Tensor, s
     _check(lib().moe_mfma_rate_probe(_ptr(operands), iters, _ptr(out), C.byref(flops),
                                      _stream(stream)), "moe_mfma_rate_probe")
     return float(flops.value)
+
+
+def moe_hbm_read_probe(data: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
+    """Launch the streaming-read probe over `data`; returns the number of bytes it reads."""
+    nbytes = data.numel() * data.element_size()
+    _check(lib().moe_hbm_read_probe(_ptr(data), C.c_size_t(nbytes), _ptr(sink), _stream(stream)),
+           "moe_hbm_read_probe")
+    cus = torch.cuda.get_device_properties(data.device).multi_processor_count
+    per_wave = nbytes // (cus * 8 * 1024 * 16) * 16
+    return per_wave * 1024 * 8 * cus
 
 
 def moe_layer(W: PackedWeights, x: torch.Tensor, logits: torch.Tensor, k: int,

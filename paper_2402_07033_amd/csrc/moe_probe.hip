@@ -49,3 +49,42 @@ extern "C" int moe_mfma_rate_probe(const void* operands, int iters, float* out, 
     if (flops) *flops = (double)blocks * 4.0 * iters * 8.0 * 16.0 * 16384.0;
     return moe_launch_status();
 }
+
+// Second probe: what does a plain streaming read get from HBM on this board?  Every
+// workgroup (8 waves) reads its contiguous share of `bytes` with fully coalesced
+// non-temporal 16-byte-per-lane loads, 16 one-KiB requests in flight per wave - the request
+// structure of the decode kernels with the set-up, the arithmetic and the epilogue removed.
+#define HBM_PROBE_RING 16
+__global__ __launch_bounds__(512) void hbm_read_kernel(const u32x4_t* __restrict__ p,
+                                                       unsigned long long loads_per_wave,
+                                                       unsigned* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    const unsigned long long wave_id = (unsigned long long)blockIdx.x * 8 + (threadIdx.x >> 6);
+    const u32x4_t* b = p + wave_id * loads_per_wave * 64 + lane;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    u32x4_t buf[HBM_PROBE_RING];
+#pragma unroll
+    for (int i = 0; i < HBM_PROBE_RING; i++) buf[i] = __builtin_nontemporal_load(b + (size_t)i * 64);
+    for (unsigned long long j = HBM_PROBE_RING; j < loads_per_wave; j += HBM_PROBE_RING) {
+#pragma unroll
+        for (int i = 0; i < HBM_PROBE_RING; i++) {
+            acc ^= buf[i];
+            buf[i] = __builtin_nontemporal_load(b + (size_t)(j + i) * 64);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < HBM_PROBE_RING; i++) acc ^= buf[i];
+    // keeps the loads alive; practically never true
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = 1u;
+}
+
+extern "C" int moe_hbm_read_probe(const void* data, size_t bytes, unsigned* sink, void* stream) {
+    if (!data || !sink || !moe_aligned16(data)) return MOE_ERR_INVALID_ARG;
+    const unsigned blocks = (unsigned)moe_num_cus();
+    // whole rings of one-KiB loads per wave; the rest of the buffer is not read
+    const size_t per_wave = bytes / ((size_t)blocks * 8 * 1024 * HBM_PROBE_RING) * HBM_PROBE_RING;
+    if (per_wave < HBM_PROBE_RING) return MOE_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(hbm_read_kernel, dim3(blocks), dim3(512), 0, (hipStream_t)stream,
+                       (const u32x4_t*)data, (unsigned long long)per_wave, sink);
+    return moe_launch_status();
+}

@@ -278,3 +278,19 @@ def test_grouped_path_is_deterministic(moe):
         again = moe.moe_layer(W, x, lg, 2, path=moe.MOE_FFN_GROUPED)["yg"]
         assert torch.equal(first, again)
     W.free()
+
+
+def test_measurement_probes_run_and_validate(moe):
+    """The two roofline probes: they launch, report what they did, and refuse bad arguments."""
+    ops = torch.randn(32768, device="cuda").to(torch.bfloat16)
+    out = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    flops = moe.moe_mfma_rate_probe(ops, 2, out)
+    assert flops > 0
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    buf = torch.zeros(96 << 20, dtype=torch.uint8, device="cuda")
+    read = moe.moe_hbm_read_probe(buf, sink)
+    torch.cuda.synchronize()
+    assert 0 < read <= buf.numel() and read % (16 * 1024) == 0
+    assert int(sink[0]) == 0
+    with pytest.raises(moe.MoeError):  # less than one ring of loads per wave
+        moe.moe_hbm_read_probe(torch.zeros(1 << 20, dtype=torch.uint8, device="cuda"), sink)
