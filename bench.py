@@ -1,18 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE expert layer hot path on one MI355X.
 
-A step = one pass of the whole hot path (moe_route -> moe_permute ->
-moe_expert_ffn -> moe_combine, through the C ABI) over one batch of synthetic,
-Mixtral-8x7B-shaped input that is already resident in HBM.  Steps rotate over
-several independent weight sets (layers) and inputs so that no step finds its
-expert matrices in the last-level cache.
+A step = one pass of the whole hot path (gating, per-expert batching, expert
+FFN, gate-weighted combine, through the C ABI) over one batch of synthetic,
+Mixtral-8x7B-shaped input that is already resident in HBM.  Decode-sized
+workloads (T <= 16) take the one-call step moe_decode_layer (three launches;
+--four-calls times moe_route -> moe_permute -> moe_expert_ffn -> moe_combine
+instead), the others the four calls.  Steps rotate over several independent
+weight sets (layers) and inputs so that no step finds its expert matrices in
+the last-level cache.
 
-Prints ONE JSON line: whole-job tokens/s, plus
-  roofline     -- the dominant kernel (first projection of moe_expert_ffn) timed
+Prints ONE JSON line.  Headline: single-token decode (decode_t1), whole-job
+tokens/s over exactly --steps steps, plus
+  roofline     -- the dominant kernel (first projection of the expert FFN) timed
                   live with HIP events on the launch stream, against HBM peak
-                  (decode-sized workloads) or bf16 MFMA peak (prefill);
+                  (decode-sized workloads) or bf16 MFMA peak (prefill), and the
+                  whole step's fraction of the same peak (whole_step_frac);
   cpu_baseline -- the fp64 CPU oracle timed on this machine's host cores on a
-                  bounded sample of the same workload (a baseline, not a target).
+                  bounded sample of the same workload (a baseline, not a target);
+  workloads    -- the other workloads of the metric (prefill_t4096, beam_t16, the
+                  32-layer stack at 1 and 512 tokens), each with its own
+                  ms_per_step, roofline block and realised per-expert counts.
+--workload NAME runs one workload alone (profiling, sweeps).
 """
 import argparse
 import ctypes as C
@@ -28,14 +37,48 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (scaled by the 1 GiB copy calibration; see the summaries under profiles/).  Static figures
-# from those profile runs, not measured by this script.
-TRAFFIC_BYTES = {
-    "decode_t1": 470.5e6,       # profiles/stream_kernels_decode_t1.txt
-    "beam_t16": 1.604e9,        # profiles/stream_kernels_beam_t16.txt (6.8 active experts)
-    "prefill_t4096": 4.82e9,    # profiles/grouped_gemm_prefill_t4096.txt (fetch 4.58 GB + write 0.24 GB)
+# Where the HBM traffic of a workload's dominant kernel comes from: the committed rocprofv3
+# summary of the same bench command (FETCH_SIZE / WRITE_SIZE means per dispatch, in KiB after
+# the copy calibration's scale: FETCH x2, WRITE x1) and the kernels of the first projection.
+# Read at run time; None when the summary or the kernel's row is missing.
+TRAFFIC_SOURCES = {
+    "decode_t1": ("stream_kernels_decode_t1.txt", (r"stream_kernel<16, 2,",)),
+    "beam_t16": ("stream_kernels_beam_t16.txt", (r"stream_kernel<16, 2,",)),
+    "e16_decode_t1": ("stream_kernels_e16_decode_t1.txt", (r"stream_kernel<16, 2,",)),
+    "prefill_t4096": ("grouped_gemm_prefill_t4096.txt", (r"gg_gemm_kernel<true", r"gg_fixup_kernel<true",
+                                                         r"gg_pack_kernel")),
+    "e16_prefill_t4096": ("grouped_gemm_e16_prefill_t4096.txt",
+                          (r"gg_gemm_kernel<true", r"gg_fixup_kernel<true", r"gg_pack_kernel")),
 }
+
+
+def traffic_from_profile(workload):
+    """HBM bytes per launch of the workload's dominant kernel(s) from profiles/<summary>."""
+    src = TRAFFIC_SOURCES.get(workload)
+    if src is None:
+        return None
+    path = os.path.join(ROOT, "profiles", src[0])
+    if not os.path.exists(path):
+        return None
+    section, kib = None, {"FETCH_SIZE": 0.0, "WRITE_SIZE": 0.0}
+    seen = set()
+    for line in open(path):
+        if line.startswith("FETCH_SIZE per dispatch"):
+            section = "FETCH_SIZE"
+        elif line.startswith("WRITE_SIZE per dispatch"):
+            section = "WRITE_SIZE"
+        elif not line.strip():
+            section = None
+        elif section and " mean=" in line:
+            name = line.strip()
+            for pref in src[1]:
+                if name.startswith(pref):
+                    kib[section] += float(line.split("mean=")[1].split()[0])
+                    seen.add((section, pref))
+    if not any(sec == "FETCH_SIZE" for sec, _ in seen):
+        return None
+    return (2.0 * kib["FETCH_SIZE"] + 1.0 * kib["WRITE_SIZE"]) * 1024.0
+
 
 WORKLOADS = {
     # name: (T, x dtype, zipf skew of the router logits, bound)
@@ -127,27 +170,46 @@ def make_inputs(torch, moe, wl, n_inputs, seed):
 
 
 class Step:
-    """Preallocated buffers + the four C-ABI calls of one step."""
+    """Preallocated buffers + the C-ABI calls of one step."""
 
-    def __init__(self, torch, moe, T, x_dtype, fused_gate=False):
+    def __init__(self, torch, moe, T, x_dtype, one_call=True, fused_gate=False):
         N = T * K
-        self.fused_gate = fused_gate and T <= 16 and x_dtype == torch.float32
+        self.one_call = (one_call and T <= 16 and N <= 64 and E <= 16 and x_dtype == torch.float32)
+        self.fused_gate = fused_gate and not self.one_call and T <= 16 and x_dtype == torch.float32
         self.ffn_path = moe.MOE_FFN_AUTO
         i32 = dict(dtype=torch.int32, device="cuda")
         f32 = dict(dtype=torch.float32, device="cuda")
         self.moe = moe
         self.idx = torch.empty((T, K), **i32)
         self.w = torch.empty((T, K), **f32)
+        # the one-call step reads the token rows directly: no gathered copy is asked for
+        xg = None if self.one_call else torch.empty((N, D), dtype=x_dtype, device="cuda")
         self.perm_out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
-                         torch.empty(N, **i32), torch.empty((N, D), dtype=x_dtype, device="cuda"))
+                         torch.empty(N, **i32), xg)
         adt = moe.MOE_BF16 if x_dtype == torch.bfloat16 else moe.MOE_F32
         self.ws = torch.empty(moe.moe_expert_ffn_workspace(N, E, D, F, adt), dtype=torch.uint8,
                               device="cuda")
-        self.yg = torch.empty((N, D), **f32)
+        self.yg = None if self.one_call else torch.empty((N, D), **f32)
         self.y = torch.empty((T, D), **f32)
+
+    @property
+    def calls(self):
+        if self.one_call:
+            return "moe_decode_layer"
+        if self.fused_gate:
+            return "moe_route_permute, moe_expert_ffn, moe_combine"
+        return "moe_route, moe_permute, moe_expert_ffn, moe_combine"
 
     def run(self, W, x, logits, ev=None, events=None, stream=0):
         moe = self.moe
+        if self.one_call:
+            if ev is not None:
+                events.record(ev[0], stream)
+            moe.moe_decode_layer(W, x, logits, K, idx=self.idx, weights=self.w, out=self.perm_out,
+                                 workspace=self.ws, y=self.y)
+            if ev is not None:
+                events.record(ev[2], stream)
+            return
         if self.fused_gate:
             moe.moe_route_permute(logits, K, x, self.idx, self.w, self.perm_out)
             counts, offsets, perm, inv_perm, xg = self.perm_out
@@ -198,23 +260,150 @@ def cpu_baseline(torch, wl, host_w, xs, lgs, budget_s=15.0):
                        f"one weight set, {t_used:.1f} s of fp64 CPU work")
 
 
-def run_stack(args, torch, moe, wl):
-    """Layer-stack workload: value = tokens/s through all layers, ms_per_step = stack time."""
-    T, L = wl["T"], (args.layers if args.layers is not None else wl["layers"])
-    steps = args.steps if args.steps is not None else (20 if T == 1 else 5)
-    warmup = args.warmup if args.warmup is not None else 2
+PATH_NAMES = {0: "fp32", 1: "stream", 2: "grouped", 3: "mid"}
+
+
+def kernel_label(moe, T, forced_path):
+    """Name of the first-projection kernel that runs for T tokens, from the library's plan."""
+    pl = moe.moe_expert_ffn_plan(T * K, E, D, F, moe.MOE_BF16, forced_path)
+    fam = PATH_NAMES.get(pl["path"], str(pl["path"]))
+    if fam == "stream":
+        return "stream_kernel, first projection (x.w1, x.w3, silu*mul)", pl
+    if fam == "mid":
+        return "gg_pack + mid_kernel<UP> + mid_fixup (x.w1, x.w3, silu*mul)", pl
+    return (f"gg_pack + gg_gemm_kernel<UP> {pl['up_tile_rows']}x{pl['up_tile_features']} tile "
+            "+ fix-up (x.w1, x.w3, silu*mul)"), pl
+
+
+def run_layer_workload(torch, moe, name, wl, sets, args, steps, warmup, host_w=None):
+    """One single-layer workload over the given (rotated) weight sets -> result dict."""
+    T = wl["T"]
+    decode_like = wl["bound"] == "hbm"
+    n_layers = len(sets)
+    n_inputs = 16 if decode_like else 2
+    xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
+    step = Step(torch, moe, T, xs[0].dtype,
+                one_call=not args.four_calls and args.ffn_path == "auto",
+                fused_gate=args.fused_gate)
+    step.ffn_path = {"auto": moe.MOE_FFN_AUTO, "stream": moe.MOE_FFN_STREAM,
+                     "grouped": moe.MOE_FFN_GROUPED, "mid": moe.MOE_FFN_MID}[args.ffn_path]
+    stream = torch.cuda.current_stream().cuda_stream
+    events = HipEvents()
+
+    def run_range(n, ev_list=None):
+        for i in range(n):
+            ev = ev_list[i] if ev_list is not None else None
+            if ev is not None:
+                moe.moe_set_ffn_mid_event(ev[1])
+            step.run(sets[i % n_layers], xs[i % n_inputs], lgs[i % n_inputs], ev, events, stream)
+
+    # realised per-expert counts of every input (outside any timed region)
+    counts_all = []
+    for i in range(n_inputs):
+        step.run(sets[0], xs[i], lgs[i])
+        torch.cuda.synchronize()
+        counts_all.append(step.perm_out[0].cpu().tolist())
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB write
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    run_range(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_range(steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    # second pass: HIP events around the two projection kernels of every step
+    ev_list = [(events.create(), events.create(), events.create()) for _ in range(steps)]
+    run_range(steps, ev_list)
+    moe.moe_set_ffn_mid_event(None)
+    torch.cuda.synchronize()
+    up_ms = sum(events.elapsed_ms(a, b) for a, b, _ in ev_list) / steps
+    dn_ms = sum(events.elapsed_ms(b, c) for _, b, c in ev_list) / steps
+    for ev in ev_list:
+        for e in ev:
+            events.destroy(e)
+
+    # algorithmic work of the dominant kernel (first projection), averaged over the steps
+    act_sets = [sum(1 for c in counts_all[i % n_inputs] if c > 0) for i in range(steps)]
+    n_active = sum(act_sets) / steps
+    label, plan = kernel_label(moe, T, step.ffn_path)
+    if step.one_call:
+        label = "gating + " + label
+    traffic = traffic_from_profile(name) if args.tokens is None and args.ffn_path == "auto" else None
+    if decode_like:
+        # bytes: w1 and w3 of every active expert, read once (2 * d * f bf16 each)
+        up_bytes = n_active * 2 * D * F * 2
+        achieved = up_bytes / (up_ms * 1e-3) / 1e9
+        whole = n_active * 3 * D * F * 2 / (ms_per_step * 1e-3) / 1e9
+        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=achieved / HBM_PEAK_GBS, traffic=traffic, kernel=label,
+                        kernel_ms=up_ms, second_projection_ms=dn_ms,
+                        second_projection_GBs=n_active * D * F * 2 / (dn_ms * 1e-3) / 1e9,
+                        mean_active_experts=n_active, whole_step_GBs=whole,
+                        whole_step_frac=whole / HBM_PEAK_GBS)
+    else:
+        up_flops = T * K * 2 * 2 * D * F  # real rows only
+        achieved = up_flops / (up_ms * 1e-3) / 1e12
+        whole = T * K * 6 * D * F / (ms_per_step * 1e-3) / 1e12
+        roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
+                        unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS, traffic=traffic,
+                        kernel=label, kernel_ms=up_ms, second_projection_ms=dn_ms,
+                        second_projection_TFLOPs=T * K * 2 * D * F / (dn_ms * 1e-3) / 1e12,
+                        whole_step_TFLOPs=whole, whole_step_frac=whole / MFMA_BF16_PEAK_TFLOPS)
+    if step.one_call:
+        roofline["second_projection_note"] = "second_projection_ms includes the combine launch"
+
+    result = {
+        "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights x " + ("bf16" if wl["x_bf16"] else
+                                      ("fp32 (bf16 hi+lo)" if plan["path"] == 1 else
+                                       "fp32 (rounded to bf16)")) +
+                 " activations, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": name, "T": T, "d_model": D, "d_ff": F, "experts": E,
+                   "top_k": K, "weight_sets_rotated": n_layers, "inputs_rotated": n_inputs,
+                   "counts_first_input": counts_all[0], "ffn_path": PATH_NAMES[plan["path"]],
+                   "calls_per_step": step.calls},
+        "roofline": roofline,
+    }
+    if host_w is not None:
+        result["cpu_baseline"] = cpu_baseline(torch, wl, host_w, xs, lgs)
+    return result
+
+
+def make_stack_layers(torch, moe, L, keep_host_first=False):
+    """L independent weight sets + router matrices (seeded), all resident."""
     g = torch.Generator(device="cuda")
     g.manual_seed(777)
     layers, host_w, host_gate = [], None, None
     for li in range(L):
         W, src = make_weight_set(torch, moe, 2000 + li)
         wg = (torch.randn((D, E), generator=g, device="cuda") * D ** -0.5).contiguous()
-        if li == 0 and not args.no_cpu_baseline:
+        if li == 0 and keep_host_first:
             host_w = tuple(t.cpu() for t in src)
             host_gate = wg.cpu()
         del src
         layers.append((W, wg))
     torch.cuda.empty_cache()
+    return layers, host_w, host_gate
+
+
+def run_stack_workload(torch, moe, name, wl, layers, args, steps, warmup, host_w=None,
+                       host_gate=None):
+    """Layer-stack workload: value = tokens/s through all layers, ms_per_step = stack time."""
+    T, L = wl["T"], len(layers)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(778)
     x0 = torch.randn((T, D), generator=g, device="cuda")
     x = torch.empty_like(x0)
     bufs = moe.StackBuffers(T, E, K, D, F)
@@ -253,27 +442,31 @@ def run_stack(args, torch, moe, wl):
     up_bytes = n_active * 2 * D * F * 2
     achieved = up_bytes / (up_ms * 1e-3) / 1e9
     all_bytes = n_active * 3 * D * F * 2
+    whole_gbs = all_bytes / (ms_per_step * 1e-3) / 1e9
+    whole_tf = T * K * 6 * D * F * L / (ms_per_step * 1e-3) / 1e12
+    label, plan = kernel_label(moe, T, moe.MOE_FFN_AUTO)
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=achieved / HBM_PEAK_GBS, traffic=None,
-                    kernel="first projection of moe_expert_ffn, summed over the layers",
+                    kernel=label + ", summed over the layers",
                     kernel_ms=up_ms, active_experts_all_layers=n_active,
-                    whole_stack_GBs=all_bytes / (ms_per_step * 1e-3) / 1e9,
-                    whole_stack_TFLOPs=T * K * 6 * D * F * L / (ms_per_step * 1e-3) / 1e12)
+                    whole_step_GBs=whole_gbs, whole_step_frac=whole_gbs / HBM_PEAK_GBS,
+                    whole_step_TFLOPs=whole_tf,
+                    whole_step_mfma_frac=whole_tf / MFMA_BF16_PEAK_TFLOPS)
     result = {
         "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights x fp32 activations" + (" (bf16 hi+lo)" if T * K <= 96 else
+        "dtype": "bf16 weights x fp32 activations" + (" (bf16 hi+lo)" if plan["path"] == 1 else
                                                       " (rounded to bf16)") + ", fp32 accumulate",
         "data": "synthetic",
-        "config": {"workload": args.workload, "T": T, "layers": L, "d_model": D, "d_ff": F,
-                   "experts": E, "top_k": K,
+        "config": {"workload": name, "T": T, "layers": L, "d_model": D, "d_ff": F,
+                   "experts": E, "top_k": K, "ffn_path": PATH_NAMES[plan["path"]],
                    "per_token_expert_time_us": ms_per_step * 1e3 / T,
                    "host_enqueue_ms": host_enqueue_ms,
                    "resident_expert_bytes": sum(W.nbytes for W, _ in layers)},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if host_w is not None:
         # the oracle on a bounded sample: up to 4 tokens through ONE layer; the stack rate is
         # that per-layer rate divided by the number of layers (labelled extrapolated)
         import numpy as np
@@ -292,7 +485,15 @@ def run_stack(args, torch, moe, wl):
             value=per_layer_tokens_s / L, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
             sample=f"{reps} x {n_tok} tokens through 1 layer ({t_used:.1f} s of fp64 CPU work); "
                    f"stack rate extrapolated as the one-layer rate / {L} layers")
-    print(json.dumps(result))
+    return result
+
+
+def nested(res):
+    """The part of a workload's result that goes into the headline line's `workloads`."""
+    keep = {k: res[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dtype")}
+    keep["config"] = res["config"]
+    keep["roofline"] = res["roofline"]
+    return keep
 
 
 def mfma_ceiling(torch, moe):
@@ -354,16 +555,21 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="decode_t1", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="all", choices=["all"] + sorted(WORKLOADS),
+                    help="all (default): decode_t1 as the headline plus prefill_t4096, beam_t16, "
+                         "stack_t1 and stack_t512 nested under `workloads`; else that one alone")
     ap.add_argument("--layers", type=int, default=None, help="independent weight sets rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=None,
                     help="override T of the workload (sweeps; the JSON names it)")
     ap.add_argument("--ffn-path", default="auto", choices=["auto", "stream", "grouped", "mid"],
-                    help="force the expert-FFN kernel family (sweeps)")
+                    help="force the expert-FFN kernel family (sweeps; implies --four-calls)")
+    ap.add_argument("--four-calls", action="store_true",
+                    help="decode-sized workloads: time moe_route, moe_permute, moe_expert_ffn, "
+                         "moe_combine instead of the one-call moe_decode_layer")
     ap.add_argument("--fused-gate", action="store_true",
-                    help="decode-sized workloads: use the one-launch moe_route_permute instead "
-                         "of moe_route + moe_permute (same outputs)")
+                    help="with --four-calls: use the one-launch moe_route_permute instead of "
+                         "moe_route + moe_permute (same outputs)")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="only measure the sustained matrix-core rate of this board")
     ap.add_argument("--hbm-ceiling", action="store_true",
@@ -390,118 +596,65 @@ def main():
         print(json.dumps({"hbm_streaming_read": hbm_ceiling(torch, moe),
                           "published_peak_GBs": HBM_PEAK_GBS}))
         return
-    wl = dict(WORKLOADS[args.workload])
+
+    def defaults(wl):
+        decode_like = wl["bound"] == "hbm"
+        if "layers" in wl:
+            return (20 if wl["T"] == 1 else 5), 2
+        return (400 if decode_like else 30), (40 if decode_like else 5)
+
     global D, F, E, K
-    D, F, E, K = wl.get("shape", (D, F, E, K))
-    if args.tokens is not None:
-        wl["T"] = args.tokens
-    T = wl["T"]
-    if "layers" in wl:
-        return run_stack(args, torch, moe, wl)
-    decode_like = wl["bound"] == "hbm"
-    steps = args.steps if args.steps is not None else (400 if decode_like else 30)
-    warmup = args.warmup if args.warmup is not None else (40 if decode_like else 5)
-    n_layers = args.layers if args.layers is not None else (8 if decode_like else 2)
-    n_inputs = 16 if decode_like else 2
+    if args.workload != "all":
+        wl = dict(WORKLOADS[args.workload])
+        D, F, E, K = wl.get("shape", (D, F, E, K))
+        if args.tokens is not None:
+            wl["T"] = args.tokens
+        d_steps, d_warm = defaults(wl)
+        steps = args.steps if args.steps is not None else d_steps
+        warmup = args.warmup if args.warmup is not None else d_warm
+        if "layers" in wl:
+            L = args.layers if args.layers is not None else wl["layers"]
+            layers, host_w, host_gate = make_stack_layers(torch, moe, L, not args.no_cpu_baseline)
+            res = run_stack_workload(torch, moe, args.workload, wl, layers, args, steps, warmup,
+                                     host_w, host_gate)
+        else:
+            decode_like = wl["bound"] == "hbm"
+            n_layers = args.layers if args.layers is not None else (8 if decode_like else 2)
+            sets, host_w = [], None
+            for li in range(n_layers):
+                W, src = make_weight_set(torch, moe, 2000 + li)
+                if li == 0 and not args.no_cpu_baseline:
+                    host_w = tuple(t.cpu() for t in src)
+                del src
+                sets.append(W)
+            torch.cuda.empty_cache()
+            res = run_layer_workload(torch, moe, args.workload, wl, sets, args, steps, warmup, host_w)
+        print(json.dumps(res))
+        return
 
-    sets, host_w = [], None
-    for li in range(n_layers):
-        W, src = make_weight_set(torch, moe, 2000 + li)
-        if li == 0 and not args.no_cpu_baseline:
-            host_w = tuple(t.cpu() for t in src)
-        del src
-        sets.append(W)
-    torch.cuda.empty_cache()
-    xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
-    step = Step(torch, moe, T, xs[0].dtype, fused_gate=args.fused_gate)
-    step.ffn_path = {"auto": moe.MOE_FFN_AUTO, "stream": moe.MOE_FFN_STREAM,
-                     "grouped": moe.MOE_FFN_GROUPED, "mid": moe.MOE_FFN_MID}[args.ffn_path]
-    stream = torch.cuda.current_stream().cuda_stream
-    events = HipEvents()
-
-    def run_range(n, ev_list=None):
-        for i in range(n):
-            ev = ev_list[i] if ev_list is not None else None
-            if ev is not None:
-                moe.moe_set_ffn_mid_event(ev[1])
-            step.run(sets[i % n_layers], xs[i % n_inputs], lgs[i % n_inputs], ev, events, stream)
-
-    # realised per-expert counts of every input (outside any timed region)
-    counts_all = []
-    for i in range(n_inputs):
-        step.run(sets[0], xs[i], lgs[i])
-        torch.cuda.synchronize()
-        counts_all.append(step.perm_out[0].cpu().tolist())
-
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB write
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    run_range(warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_range(steps)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / steps
-
-    # second pass: HIP events around the two projection kernels of every step
-    ev_list = [(events.create(), events.create(), events.create()) for _ in range(steps)]
-    run_range(steps, ev_list)
-    moe.moe_set_ffn_mid_event(None)
-    torch.cuda.synchronize()
-    up_ms = sum(events.elapsed_ms(a, b) for a, b, _ in ev_list) / steps
-    dn_ms = sum(events.elapsed_ms(b, c) for _, b, c in ev_list) / steps
-    for ev in ev_list:
-        for e in ev:
-            events.destroy(e)
-
-    # algorithmic work of the dominant kernel (first projection), averaged over the steps
-    act_sets = [sum(1 for c in counts_all[i % n_inputs] if c > 0) for i in range(steps)]
-    n_active = sum(act_sets) / steps
-    if decode_like:
-        # bytes: w1 and w3 of every active expert, read once (2 * d * f bf16 each)
-        up_bytes = n_active * 2 * D * F * 2
-        achieved = up_bytes / (up_ms * 1e-3) / 1e9
-        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=achieved / HBM_PEAK_GBS, traffic=TRAFFIC_BYTES.get(args.workload),
-                        kernel="stream_kernel<KSW=16,NMAT=2> (x.w1, x.w3, silu*mul)",
-                        kernel_ms=up_ms, second_projection_ms=dn_ms,
-                        second_projection_GBs=n_active * D * F * 2 / (dn_ms * 1e-3) / 1e9,
-                        mean_active_experts=n_active)
-    else:
-        up_flops = T * K * 2 * 2 * D * F  # real rows only
-        achieved = up_flops / (up_ms * 1e-3) / 1e12
-        roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_BF16_PEAK_TFLOPS,
-                        unit="TFLOP/s", frac=achieved / MFMA_BF16_PEAK_TFLOPS,
-                        traffic=TRAFFIC_BYTES.get(args.workload),
-                        kernel="gg_pack + gg_gemm_kernel<UP> (x.w1, x.w3, silu*mul)",
-                        kernel_ms=up_ms, second_projection_ms=dn_ms,
-                        second_projection_TFLOPs=T * K * 2 * D * F / (dn_ms * 1e-3) / 1e12,
-                        layer_TFLOPs=T * K * 6 * D * F / (ms_per_step * 1e-3) / 1e12)
-
-    result = {
-        "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights x " + ("bf16" if wl["x_bf16"] else "fp32 (bf16 hi+lo)") +
-                 " activations, fp32 accumulate",
-        "data": "synthetic",
-        "config": {"workload": args.workload, "T": T, "d_model": D, "d_ff": F, "experts": E,
-                   "top_k": K, "weight_sets_rotated": n_layers, "inputs_rotated": n_inputs,
-                   "counts_first_input": counts_all[0], "ffn_path": args.ffn_path,
-                   "calls_per_step": ("moe_route_permute, moe_expert_ffn, moe_combine"
-                                      if step.fused_gate else
-                                      "moe_route, moe_permute, moe_expert_ffn, moe_combine")},
-        "roofline": roofline,
-    }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(torch, wl, host_w, xs, lgs)
-    print(json.dumps(result))
+    # ---- default: every workload of the metric in one line ----------------------------
+    # One resident set of 32 layers (90 GB) serves all of them: the stack workloads use all,
+    # the single-layer ones rotate over the first 8 (decode-sized) or 2 (prefill).
+    L = args.layers if args.layers is not None else 32
+    layers, host_w, _ = make_stack_layers(torch, moe, L, not args.no_cpu_baseline)
+    sets = [W for W, _ in layers]
+    head_wl = dict(WORKLOADS["decode_t1"])
+    d_steps, d_warm = defaults(head_wl)
+    steps = args.steps if args.steps is not None else d_steps
+    warmup = args.warmup if args.warmup is not None else d_warm
+    res = run_layer_workload(torch, moe, "decode_t1", head_wl, sets[:8], args, steps, warmup, host_w)
+    others = {}
+    for name in ("prefill_t4096", "beam_t16"):
+        wl = dict(WORKLOADS[name])
+        st, wu = defaults(wl)
+        n_sets = 8 if wl["bound"] == "hbm" else 2
+        others[name] = nested(run_layer_workload(torch, moe, name, wl, sets[:n_sets], args, st, wu))
+    for name in ("stack_t1", "stack_t512"):
+        wl = dict(WORKLOADS[name])
+        st, wu = defaults(wl)
+        others[name] = nested(run_stack_workload(torch, moe, name, wl, layers, args, st, wu))
+    res["workloads"] = others
+    print(json.dumps(res))
 
 
 if __name__ == "__main__":

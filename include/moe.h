@@ -126,8 +126,8 @@ size_t moe_expert_ffn_workspace(int N, int E, int d, int f, moe_dtype_t act_dtyp
  * bf16-weight kernels multiply on the bf16 matrix cores: fp32 activations are
  * split into bf16 high and low parts (STREAM path, ~2^-16 relative) or rounded
  * to bf16 (GROUPED path); the intermediate silu(a)*b is kept in fp32 (STREAM)
- * or bf16 (GROUPED).  The STREAM path adds partial sums of the second
- * projection with fp32 atomics, so its low-order bits may differ run to run.
+ * or bf16 (GROUPED).  Every path adds its partial sums in a fixed order: the
+ * same inputs give the same bits on every run.
  */
 int moe_expert_ffn(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
                    const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
@@ -139,6 +139,39 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
                         size_t workspace_bytes, float* yg, int path, void* stream);
 
 /*
+ * What moe_expert_ffn_path would run for these sizes (HOST query; nothing is launched).
+ *   path     the kernel family (AUTO resolved; MOE_FFN_AUTO for fp32 weights, which have
+ *            one kernel pair of their own)
+ *   n_parts  reduction parts of the second projection that moe_expert_ffn_parts leaves
+ *            unsummed (1 unless STREAM)
+ *   up_* / down_*  GROUPED: token rows x output features of the workgroup tile of the
+ *            first / second projection (0 otherwise).  The first projection's features
+ *            count w1 and w3 columns together.
+ * Returns MOE_ERR_UNSUPPORTED if a forced family cannot run the shape.
+ */
+typedef struct {
+    int path;
+    int n_parts;
+    int up_tile_rows, up_tile_features;
+    int down_tile_rows, down_tile_features;
+} moe_ffn_plan_t;
+int moe_expert_ffn_plan(int N, int E, int d, int f, moe_dtype_t w_dtype, int path,
+                        moe_ffn_plan_t* plan);
+
+/*
+ * moe_expert_ffn for a consumer that adds the second projection's reduction parts itself
+ * (moe_combine_parts, moe_combine_norm_route_permute): the decode kernels cut the long
+ * reduction over f into parts and a separate launch would otherwise add them.
+ *   yg_parts  [max_parts][N,d] fp32 out: slab p holds part p's partial sums; the layer's
+ *             yg is slab 0 + slab 1 + ... in that order
+ *   n_parts   HOST out: slabs written (1 for every path but STREAM: then slab 0 is yg)
+ * MOE_ERR_INVALID_ARG if the shape needs more than max_parts (see moe_expert_ffn_plan).
+ */
+int moe_expert_ffn_parts(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                         const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
+                         float* yg_parts, int max_parts, int* n_parts, void* stream);
+
+/*
  * Expert outputs return to token order, weighted by the gate (Sec. 3.2 names
  * the return of expert outputs; the weighting is the Mixtral layer's):
  *     y[t,:] = sum_{j=0..k-1, ascending} weights[t,j] * yg[inv_perm[t*k+j], :]
@@ -146,6 +179,35 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
  */
 int moe_combine(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
                 int d, float* y, void* stream);
+/*
+ * The same over unsummed reduction parts (see moe_expert_ffn_parts), in one launch:
+ *     v_j    = yg_parts[0][inv_perm[t*k+j], :] + yg_parts[1][...] + ...   (part order)
+ *     y[t,:] = (residual ? y[t,:] : 0) + sum_j weights[t,j] * v_j
+ *   yg_parts [n_parts][T*k,d] fp32; yg [T*k,d] fp32 out or NULL: receives the summed rows;
+ *   y, yg must not overlap yg_parts.
+ */
+int moe_combine_parts(const float* yg_parts, int n_parts, const int32_t* inv_perm,
+                      const float* weights, int T, int k, int d, float* y, int residual,
+                      float* yg, void* stream);
+
+/*
+ * One decode step of the layer in three launches (Sec. 3.3 "Execution" for a handful of
+ * tokens, where every launch is a few percent of the step): the first-projection kernel runs
+ * the gating function and the per-expert batching in its prologue and reads the token rows
+ * directly, the second projection leaves its reduction parts, and the combine adds them.
+ * Same results as moe_route + moe_permute + moe_expert_ffn + moe_combine: index outputs bit
+ * for bit, y and yg in the same fixed summation order.
+ *   x [T,d] fp32, logits [T,E] fp32; bf16 weights; 1 <= T <= 16, E <= 16, T*k <= 64 and a
+ *   shape the STREAM family supports (MOE_ERR_UNSUPPORTED otherwise)
+ *   idx, weights, counts, offsets, perm, inv_perm: as moe_route / moe_permute, all written
+ *   xg [T*k,d] fp32 out or NULL, yg [T*k,d] fp32 out or NULL: written only when given
+ *   workspace >= moe_expert_ffn_workspace(T*k, E, d, f, MOE_F32)
+ *   y [T,d] fp32 out.  Outputs must not overlap x or logits.
+ */
+int moe_decode_layer(const moe_weights_t* W, const float* x, const float* logits, int T, int k,
+                     int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
+                     int32_t* perm, int32_t* inv_perm, float* xg, void* workspace,
+                     size_t workspace_bytes, float* yg, float* y, void* stream);
 
 /*
  * Support steps of the layer-stack workload (non-expert glue the paper keeps
@@ -182,11 +244,16 @@ int moe_rmsnorm_router_logits(const float* x, const float* w_gate, int T, int d,
  *                                          yg_prev[inv_perm_prev[t*k_prev+j], :],
  *                           then moe_norm_route_permute of x_out for the next block.
  *                           Same limits (T <= 4, E <= 16) and the same fp32 arithmetic as
- *                           the two separate calls.  Every workgroup reads the inputs while
- *                           one writes the outputs, so x_out must not be x_in, and
- *                           inv_perm / weights / xg must not be inv_perm_prev /
- *                           weights_prev / yg_prev (MOE_ERR_INVALID_ARG otherwise); the
- *                           caller keeps two sets of routing buffers and alternates.
+ *                           the two separate calls.  yg_prev may be the unsummed reduction
+ *                           parts that moe_expert_ffn_parts leaves: n_parts_prev slabs of
+ *                           [T*k_prev, d] floats, added in part order (1: the plain yg; more
+ *                           than 4: MOE_ERR_UNSUPPORTED).
+ * Aliasing: in the three calls that normalise or gather (all but moe_combine_residual)
+ * every workgroup reads the inputs while one writes the outputs, so no output may overlap
+ * an input: h, xg (and x_out) must not overlap x (x_in) or yg_prev, and inv_perm / weights
+ * must not overlap inv_perm_prev / weights_prev (MOE_ERR_INVALID_ARG otherwise; the caller
+ * of the seam call keeps two sets of routing buffers and alternates).  w_gate must be
+ * 16-byte aligned.
  */
 int moe_route_permute(const float* logits, int T, int E, int k, const float* x, int d,
                       int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
@@ -197,46 +264,13 @@ int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, in
                            int32_t* inv_perm, float* xg, void* stream);
 int moe_combine_residual(const float* yg, const int32_t* inv_perm, const float* weights, int T,
                          int k, int d, float* x, void* stream);
-int moe_combine_norm_route_permute(const float* yg_prev, const int32_t* inv_perm_prev,
+int moe_combine_norm_route_permute(const float* yg_prev, int n_parts_prev,
+                                   const int32_t* inv_perm_prev,
                                    const float* weights_prev, int k_prev, const float* x_in,
                                    float* x_out, const float* w_gate, int T, int d, int E, int k,
                                    float eps, float* h, float* logits, int32_t* idx, float* weights,
                                    int32_t* counts, int32_t* offsets, int32_t* perm,
                                    int32_t* inv_perm, float* xg, void* stream);
-
-/*
- * Measurement hook: when `hip_event` (a hipEvent_t as void*, HOST handle) is
- * non-NULL, every following moe_expert_ffn call records it on its stream
- * between the first projection (x.w1, x.w3, silu*mul) and the second (h.w2),
- * so a caller bracketing the call with its own events can time the two kernels
- * separately.  NULL switches the hook off.  Process-wide, not thread-safe.
- */
-int moe_set_ffn_mid_event(void* hip_event);
-
-/*
- * Measurement probe (not part of the layer): runs `iters` rounds of a
- * register-resident v_mfma_f32_16x16x32_bf16 loop with no memory traffic on every
- * CU and reports the flop count, so that a caller timing it with events learns the
- * matrix-core rate this board sustains for the given operand bits (the published
- * peak assumes the maximum clock; the board lowers it under load, more so for
- * random operands than for constant ones).
- *   operands  64 KiB of bf16 bit patterns (DEVICE), 16-byte aligned
- *   out       2 * CUs * 256 floats of scratch (DEVICE; 512 * 256 floats suffice)
- *   flops     HOST pointer that receives the flop count of the launch (may be NULL)
- */
-int moe_mfma_rate_probe(const void* operands, int iters, float* out, double* flops,
-                        void* stream);
-
-/* Measurement probe: one launch of a plain streaming-read kernel (one workgroup of 8 waves
- * per CU, contiguous shares, 16 one-KiB non-temporal requests in flight per wave) - the
- * request structure of the decode kernels without set-up, arithmetic or epilogue; context for
- * the HBM roofline (what fraction of the published 8 TB/s a pure read reaches on this board).
- *   data   buffer to read (DEVICE), 16-byte aligned
- *   bytes  its size; reads floor(bytes / (CUs * 8 * 16 KiB)) * 16 KiB per wave (at least
- *          16 KiB per wave, else MOE_ERR_INVALID_ARG), so slightly less than `bytes`
- *   sink   4 bytes (DEVICE) that keep the loads alive
- */
-int moe_hbm_read_probe(const void* data, size_t bytes, unsigned* sink, void* stream);
 
 #ifdef __cplusplus
 }

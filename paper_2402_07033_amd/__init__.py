@@ -5,21 +5,25 @@ Every step runs in hand-written HIP kernels; PyTorch only provides device
 memory and streams.  There is no CPU fallback: importing the binding's
 functions without the built library raises.
 """
-from .binding import (StackBuffers, moe_route_permute, moe_norm_route_permute,
-                      moe_combine_residual, moe_combine_norm_route_permute, moe_mfma_rate_probe, moe_hbm_read_probe, moe_stack_forward, MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID, MOE_FFN_STREAM,
-                      MoeError, PackedWeights, lib, lib_path, moe_combine, moe_expert_ffn,
-                      moe_expert_ffn_workspace, moe_layer, moe_permute, moe_residual_add,
-                      moe_rmsnorm, moe_rmsnorm_router_logits, moe_route, moe_router_logits, moe_set_ffn_mid_event,
-                      moe_status_string,
-                      moe_weights_free, moe_weights_pack)
+from .binding import (MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID,
+                      MOE_FFN_STREAM, MoeError, PackedWeights, StackBuffers, lib, lib_path,
+                      moe_combine, moe_combine_norm_route_permute, moe_combine_parts,
+                      moe_combine_residual, moe_decode_layer, moe_expert_ffn,
+                      moe_expert_ffn_parts, moe_expert_ffn_plan, moe_expert_ffn_workspace,
+                      moe_hbm_read_probe, moe_layer, moe_mfma_rate_probe,
+                      moe_norm_route_permute, moe_permute, moe_residual_add, moe_rmsnorm,
+                      moe_rmsnorm_router_logits, moe_route, moe_route_permute,
+                      moe_router_logits, moe_set_ffn_mid_event, moe_stack_forward,
+                      moe_status_string, moe_weights_free, moe_weights_pack)
 
 __all__ = [
-    "StackBuffers", "moe_stack_forward", "moe_route_permute", "moe_norm_route_permute",
-    "moe_combine_residual", "moe_combine_norm_route_permute", "moe_mfma_rate_probe",
-    "moe_hbm_read_probe",
-    "MOE_BF16", "MOE_F32", "MOE_FFN_AUTO", "MOE_FFN_GROUPED", "MOE_FFN_MID", "MOE_FFN_STREAM", "MoeError",
-    "PackedWeights", "lib", "lib_path", "moe_combine", "moe_expert_ffn",
-    "moe_expert_ffn_workspace", "moe_layer", "moe_permute", "moe_residual_add", "moe_rmsnorm",
-    "moe_rmsnorm_router_logits", "moe_route", "moe_router_logits", "moe_set_ffn_mid_event", "moe_status_string", "moe_weights_free",
+    "MOE_BF16", "MOE_F32", "MOE_FFN_AUTO", "MOE_FFN_GROUPED", "MOE_FFN_MID", "MOE_FFN_STREAM",
+    "MoeError", "PackedWeights", "StackBuffers", "lib", "lib_path", "moe_combine",
+    "moe_combine_norm_route_permute", "moe_combine_parts", "moe_combine_residual",
+    "moe_decode_layer", "moe_expert_ffn", "moe_expert_ffn_parts", "moe_expert_ffn_plan",
+    "moe_expert_ffn_workspace", "moe_hbm_read_probe", "moe_layer", "moe_mfma_rate_probe",
+    "moe_norm_route_permute", "moe_permute", "moe_residual_add", "moe_rmsnorm",
+    "moe_rmsnorm_router_logits", "moe_route", "moe_route_permute", "moe_router_logits",
+    "moe_set_ffn_mid_event", "moe_stack_forward", "moe_status_string", "moe_weights_free",
     "moe_weights_pack",
 ]

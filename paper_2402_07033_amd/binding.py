@@ -16,13 +16,22 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libmoe_hip.so")
 _lib = None
 
+# entry points of include/moe.h and of include/moe_probe.h
 EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
-           "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
-           "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
-           "moe_mfma_rate_probe", "moe_hbm_read_probe", "moe_route_permute",
+           "moe_expert_ffn", "moe_expert_ffn_path", "moe_expert_ffn_plan",
+           "moe_expert_ffn_parts", "moe_combine", "moe_combine_parts", "moe_decode_layer",
+           "moe_rmsnorm", "moe_router_logits", "moe_residual_add", "moe_route_permute",
            "moe_norm_route_permute", "moe_combine_residual", "moe_combine_norm_route_permute",
            "moe_rmsnorm_router_logits")
+PROBE_EXPORTS = ("moe_set_ffn_mid_event", "moe_mfma_rate_probe", "moe_hbm_read_probe")
+
+
+class FfnPlan(C.Structure):
+    """moe_ffn_plan_t."""
+    _fields_ = [("path", C.c_int), ("n_parts", C.c_int),
+                ("up_tile_rows", C.c_int), ("up_tile_features", C.c_int),
+                ("down_tile_rows", C.c_int), ("down_tile_features", C.c_int)]
 
 
 class MoeError(RuntimeError):
@@ -75,9 +84,18 @@ def lib():
         L.moe_norm_route_permute.restype = C.c_int
         L.moe_combine_residual.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
         L.moe_combine_residual.restype = C.c_int
-        L.moe_combine_norm_route_permute.argtypes = ([vp, vp, vp, i32, vp, vp, vp] + [i32] * 4 +
+        L.moe_combine_norm_route_permute.argtypes = ([vp, i32, vp, vp, i32, vp, vp, vp] + [i32] * 4 +
                                                      [f32] + [vp] * 10)
         L.moe_combine_norm_route_permute.restype = C.c_int
+        L.moe_expert_ffn_plan.argtypes = [i32] * 6 + [C.POINTER(FfnPlan)]
+        L.moe_expert_ffn_plan.restype = C.c_int
+        L.moe_expert_ffn_parts.argtypes = [vp, vp, i32, vp, i32, vp, C.c_size_t, vp, i32,
+                                           C.POINTER(C.c_int), vp]
+        L.moe_expert_ffn_parts.restype = C.c_int
+        L.moe_combine_parts.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, i32, vp, vp]
+        L.moe_combine_parts.restype = C.c_int
+        L.moe_decode_layer.argtypes = [vp, vp, vp, i32, i32] + [vp] * 8 + [C.c_size_t, vp, vp, vp]
+        L.moe_decode_layer.restype = C.c_int
         for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
                   "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
                   "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
@@ -222,6 +240,85 @@ def moe_expert_ffn(W: PackedWeights, xg: torch.Tensor, offsets: torch.Tensor, wo
     return yg
 
 
+def moe_expert_ffn_plan(N: int, E: int, d: int, f: int, w_dtype: int = MOE_BF16,
+                        path: int = MOE_FFN_AUTO) -> dict:
+    """What moe_expert_ffn would run for these sizes: kernel family, reduction parts,
+    GROUPED tile shapes (host query)."""
+    pl = FfnPlan()
+    _check(lib().moe_expert_ffn_plan(N, E, d, f, w_dtype, path, C.byref(pl)), "moe_expert_ffn_plan")
+    return {n: getattr(pl, n) for n, _ in FfnPlan._fields_}
+
+
+def moe_expert_ffn_parts(W: "PackedWeights", xg: torch.Tensor, offsets: torch.Tensor, yg_parts,
+                         workspace=None, stream=None) -> int:
+    """moe_expert_ffn that leaves the second projection's reduction parts unsummed in
+    yg_parts [max_parts, N, d]; returns the number of slabs written."""
+    _dev(offsets, torch.int32, "offsets")
+    _dev(yg_parts, torch.float32, "yg_parts")
+    N = xg.shape[0]
+    adt = _act_dtype(xg)
+    if workspace is None:
+        need = moe_expert_ffn_workspace(N, W.E, W.d, W.f, adt)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=xg.device)
+    n = C.c_int(0)
+    _check(lib().moe_expert_ffn_parts(C.c_void_p(W.handle), _ptr(xg), adt, _ptr(offsets), N,
+                                      _ptr(workspace), workspace.numel(), _ptr(yg_parts),
+                                      yg_parts.shape[0], C.byref(n), _stream(stream)),
+           "moe_expert_ffn_parts")
+    return int(n.value)
+
+
+def moe_combine_parts(yg_parts: torch.Tensor, n_parts: int, inv_perm: torch.Tensor,
+                      weights: torch.Tensor, y=None, residual: bool = False, yg=None, stream=None):
+    """y[t] (+)= sum_j weights[t,j] * sum_p yg_parts[p, inv_perm[t*k+j]]; yg (optional)
+    receives the summed rows."""
+    _dev(yg_parts, torch.float32, "yg_parts")
+    T, k = weights.shape
+    d = yg_parts.shape[-1]
+    if y is None:
+        if residual:
+            raise ValueError("residual=True needs y")
+        y = torch.empty((T, d), dtype=torch.float32, device=yg_parts.device)
+    _check(lib().moe_combine_parts(_ptr(yg_parts), n_parts, _ptr(inv_perm), _ptr(weights), T, k, d,
+                                   _ptr(y), int(residual), _ptr(yg), _stream(stream)),
+           "moe_combine_parts")
+    return y
+
+
+def moe_decode_layer(W: "PackedWeights", x: torch.Tensor, logits: torch.Tensor, k: int, idx=None,
+                     weights=None, out=None, workspace=None, yg=None, y=None, want_xg=False,
+                     stream=None) -> dict:
+    """One decode step (T <= 16) in three launches: gate + first projection, second
+    projection, combine.  `out` = (counts, offsets, perm, inv_perm, xg-or-None)."""
+    _dev(x, torch.float32, "x")
+    _dev(logits, torch.float32, "logits")
+    T, d = x.shape
+    E = logits.shape[1]
+    N = T * k
+    dev = x.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    if idx is None:
+        idx = torch.empty((T, k), **i32)
+    if weights is None:
+        weights = torch.empty((T, k), dtype=torch.float32, device=dev)
+    if out is None:
+        out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
+               torch.empty(N, **i32),
+               torch.empty((N, d), dtype=torch.float32, device=dev) if want_xg else None)
+    counts, offsets, perm, inv_perm, xg = out
+    if workspace is None:
+        workspace = torch.empty(max(moe_expert_ffn_workspace(N, W.E, W.d, W.f, MOE_F32), 256),
+                                dtype=torch.uint8, device=dev)
+    if y is None:
+        y = torch.empty((T, d), dtype=torch.float32, device=dev)
+    _check(lib().moe_decode_layer(C.c_void_p(W.handle), _ptr(x), _ptr(logits), T, k, _ptr(idx),
+                                  _ptr(weights), _ptr(counts), _ptr(offsets), _ptr(perm),
+                                  _ptr(inv_perm), _ptr(xg), _ptr(workspace), workspace.numel(),
+                                  _ptr(yg), _ptr(y), _stream(stream)), "moe_decode_layer")
+    return dict(idx=idx, w=weights, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm,
+                xg=xg, yg=yg, y=y)
+
+
 def moe_combine(yg: torch.Tensor, inv_perm: torch.Tensor, weights: torch.Tensor, y=None,
                 stream=None):
     """yg fp32 [N,d], inv_perm int32 [N], weights fp32 [T,k] -> y fp32 [T,d]."""
@@ -351,15 +448,17 @@ def moe_combine_residual(yg: torch.Tensor, inv_perm: torch.Tensor, weights: torc
 
 
 def moe_combine_norm_route_permute(yg_prev, inv_perm_prev, weights_prev, x_in, x_out, w_gate,
-                                   k: int, eps: float, h, logits, idx, weights, out, stream=None):
+                                   k: int, eps: float, h, logits, idx, weights, out, stream=None,
+                                   n_parts_prev: int = 1):
     """Seam between two blocks in one launch: x_out = x_in + combine(yg_prev), then the
-    fused front end of the next block on x_out (T <= 4).  Outputs must not alias the
-    *_prev inputs."""
+    fused front end of the next block on x_out (T <= 4).  yg_prev may hold n_parts_prev
+    unsummed reduction parts.  Outputs must not alias the *_prev inputs."""
     T, d = x_in.shape
     E = w_gate.shape[1]
     counts, offsets, perm, inv_perm, xg = out
     _check(lib().moe_combine_norm_route_permute(
-        _ptr(yg_prev), _ptr(inv_perm_prev), _ptr(weights_prev), weights_prev.shape[1], _ptr(x_in),
+        _ptr(yg_prev), n_parts_prev, _ptr(inv_perm_prev), _ptr(weights_prev), weights_prev.shape[1],
+        _ptr(x_in),
         _ptr(x_out), _ptr(w_gate), T, d, E, k, eps, _ptr(h), _ptr(logits), _ptr(idx),
         _ptr(weights), _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(xg),
         _stream(stream)), "moe_combine_norm_route_permute")
@@ -387,7 +486,10 @@ class StackBuffers:
         self.x_alt = torch.empty((T, d), **f32)
         self.ws = torch.empty(max(moe_expert_ffn_workspace(N, E, d, f, MOE_F32), 256),
                               dtype=torch.uint8, device=device)
-        self.yg = torch.empty((N, d), **f32)
+        # the second projection's reduction parts (decode kernels; slab 0 is yg otherwise)
+        self.max_parts = max(1, moe_expert_ffn_plan(N, E, d, f, MOE_BF16)["n_parts"])
+        self.yg_parts = torch.empty((self.max_parts, N, d), **f32)
+        self.yg = self.yg_parts[0]
         self.y = torch.empty((T, d), **f32)
 
 
@@ -401,7 +503,8 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
     is called before each layer's expert FFN is enqueued (measurement hook).  fused=True
     uses the one-launch front end (T <= 4) and combine+residual, and with seam=True also
     folds each block's combine+residual into the next block's front end; fused=False the
-    separate calls."""
+    separate calls.  The fused variants leave the second projection's reduction parts
+    unsummed and add them inside the combine (no separate launch)."""
     _dev(x, torch.float32, "x")
     T, d = x.shape
     W0 = layers[0][0]
@@ -409,15 +512,19 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
         bufs = StackBuffers(T, W0.E, k, d, W0.f, x.device)
     fused_gate = fused and T <= 4 and W0.E <= 16
     seam = seam and fused_gate
+    # the seam kernel adds at most 4 parts
+    use_parts = fused and (not seam or bufs.max_parts <= 4)
+    n_parts = 1
     cur = x  # residual stream: alternates between x and bufs.x_alt across seams
     for li, (W, w_gate) in enumerate(layers):
         rs = bufs.sets[li & 1]
         if fused_gate and seam and li > 0:
             prev = bufs.sets[(li - 1) & 1]
             nxt = bufs.x_alt if cur is x else x
-            moe_combine_norm_route_permute(bufs.yg, prev["perm_out"][3], prev["w"], cur, nxt,
+            moe_combine_norm_route_permute(bufs.yg_parts, prev["perm_out"][3], prev["w"], cur, nxt,
                                            w_gate, k, eps, bufs.h, bufs.logits, rs["idx"],
-                                           rs["w"], rs["perm_out"], stream=stream)
+                                           rs["w"], rs["perm_out"], stream=stream,
+                                           n_parts_prev=n_parts)
             cur = nxt
             _, offsets, _, inv_perm, xg = rs["perm_out"]
         elif fused_gate:
@@ -439,10 +546,17 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
             idx_out.append(rs["idx"].clone())
         if on_layer is not None:
             on_layer(li)
-        moe_expert_ffn(W, xg, offsets, workspace=bufs.ws, yg=bufs.yg, stream=stream)
+        if use_parts:
+            n_parts = moe_expert_ffn_parts(W, xg, offsets, bufs.yg_parts, workspace=bufs.ws,
+                                           stream=stream)
+        else:
+            moe_expert_ffn(W, xg, offsets, workspace=bufs.ws, yg=bufs.yg, stream=stream)
         if seam and li + 1 < len(layers):
             continue  # folded into the next block's front end
-        if fused:
+        if fused and n_parts > 1:
+            moe_combine_parts(bufs.yg_parts, n_parts, inv_perm, rs["w"], y=cur, residual=True,
+                              stream=stream)
+        elif fused:
             moe_combine_residual(bufs.yg, inv_perm, rs["w"], cur, stream=stream)
         else:
             moe_combine(bufs.yg, inv_perm, rs["w"], bufs.y, stream=stream)

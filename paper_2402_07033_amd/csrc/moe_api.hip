@@ -14,14 +14,29 @@ static inline bool tek_ok(int T, int E, int k) {
 }
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-hipEvent_t g_moe_mid_event = nullptr;
+// Do two byte ranges overlap?
+static inline bool ranges_overlap(const void* a, size_t an, const void* b, size_t bn) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a && b && a0 < b0 + bn && b0 < a0 + an;
+}
+
+// AUTO's choice of kernel family (measured crossovers, Mixtral shape and the 16-expert shape,
+// Zipf-skewed routing; with balanced routing each kernel stays ahead somewhat longer than its
+// limit here):
+//   up to 72 routed rows the decode kernels, which stream each active expert once per
+//   16-row tile at ~6.5 TB/s;
+//   up to MOE_MID_MAX_ROWS rows per expert on average the weight-streaming grouped GEMM
+//   (many experts with a handful of rows each: 11 % ahead at 6 rows per expert, 5 % behind
+//   at 12; with 8 experts the window is 73..80 rows, so this is a path of E >= 16 layers);
+//   above that the LDS-tiled grouped GEMM, whose smaller tiles stream the weights too.
+static int auto_path(int N, int E, int d, int f) {
+    if (N <= 72 && moe_ffn_stream_supported(d, f)) return MOE_FFN_STREAM;
+    if ((long long)N <= (long long)MOE_MID_MAX_ROWS * E && moe_ffn_mid_supported(N, E, d, f))
+        return MOE_FFN_MID;
+    return MOE_FFN_GROUPED;
+}
 
 extern "C" {
-
-int moe_set_ffn_mid_event(void* hip_event) {
-    g_moe_mid_event = (hipEvent_t)hip_event;
-    return MOE_OK;
-}
 
 const char* moe_status_string(int status) {
     switch (status) {
@@ -110,25 +125,9 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
         if (act_dtype != MOE_F32 || path != MOE_FFN_AUTO) return MOE_ERR_UNSUPPORTED;
         return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
     }
-    if (path == MOE_FFN_AUTO) {
-        // Measured crossovers (Mixtral shape and the 16-expert shape, Zipf-skewed routing; with
-        // balanced routing each kernel stays ahead somewhat longer than its limit here):
-        //   up to 72 routed rows the decode kernels, which stream each active expert once
-        //   per 16-row tile at ~6.5 TB/s;
-        //   up to MOE_MID_MAX_ROWS rows per expert on average the weight-streaming grouped
-        //   GEMM (many experts with a handful of rows each: 11 % ahead at 6 rows per expert,
-        //   5 % behind at 12);
-        //   above that the LDS-tiled grouped GEMM, whose smaller tiles stream the weights too.
-        if (N <= 72 && moe_ffn_stream_supported(W->d, W->f))
-            path = MOE_FFN_STREAM;
-        else if ((long long)N <= (long long)MOE_MID_MAX_ROWS * W->E &&
-                 moe_ffn_mid_supported(N, W->E, W->d, W->f))
-            path = MOE_FFN_MID;
-        else
-            path = MOE_FFN_GROUPED;
-    }
+    if (path == MOE_FFN_AUTO) path = auto_path(N, W->E, W->d, W->f);
     if (path == MOE_FFN_STREAM)
-        return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
+        return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg, nullptr, s);
     if (path == MOE_FFN_MID)
         return moe_ffn_mid_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
     return moe_ffn_grouped_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
@@ -139,6 +138,106 @@ int moe_expert_ffn(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype
                    float* yg, void* stream) {
     return moe_expert_ffn_path(W, xg, act_dtype, offsets, N, workspace, workspace_bytes, yg,
                                MOE_FFN_AUTO, stream);
+}
+
+int moe_expert_ffn_plan(int N, int E, int d, int f, moe_dtype_t w_dtype, int path,
+                        moe_ffn_plan_t* plan) {
+    if (!plan || N < 0 || N >= MOE_MAX_N || E < 1 || E > MOE_MAX_E || !dims_ok(d) || !dims_ok(f))
+        return MOE_ERR_INVALID_ARG;
+    if (w_dtype != MOE_F32 && w_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (path != MOE_FFN_AUTO && path != MOE_FFN_STREAM && path != MOE_FFN_GROUPED &&
+        path != MOE_FFN_MID)
+        return MOE_ERR_INVALID_ARG;
+    *plan = moe_ffn_plan_t{};
+    plan->n_parts = 1;
+    if (w_dtype == MOE_F32) {
+        if (path != MOE_FFN_AUTO) return MOE_ERR_UNSUPPORTED;
+        plan->path = MOE_FFN_AUTO;  // the all-fp32 kernels are no family of their own
+        return MOE_OK;
+    }
+    if (path == MOE_FFN_AUTO) path = auto_path(N, E, d, f);
+    plan->path = path;
+    if (path == MOE_FFN_STREAM) {
+        if (!moe_ffn_stream_supported(d, f)) return MOE_ERR_UNSUPPORTED;
+        plan->n_parts = moe_ffn_stream_parts(d, f);
+    } else if (path == MOE_FFN_MID) {
+        if (!moe_ffn_mid_supported(N, E, d, f)) return MOE_ERR_UNSUPPORTED;
+    } else {
+        return moe_ffn_grouped_plan(N, E, d, f, plan);
+    }
+    return MOE_OK;
+}
+
+int moe_expert_ffn_parts(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                         const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
+                         float* yg_parts, int max_parts, int* n_parts, void* stream) {
+    if (!W || !n_parts || max_parts < 1) return MOE_ERR_INVALID_ARG;
+    *n_parts = 1;
+    if (N < 0 || N >= MOE_MAX_N) return MOE_ERR_INVALID_ARG;
+    const bool stream_path = W->dtype == MOE_BF16 && auto_path(N, W->E, W->d, W->f) == MOE_FFN_STREAM;
+    if (!stream_path || N == 0)
+        return moe_expert_ffn_path(W, xg, act_dtype, offsets, N, workspace, workspace_bytes,
+                                   yg_parts, MOE_FFN_AUTO, stream);
+    if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (!offsets || !xg || !yg_parts || !moe_aligned16(xg) || !moe_aligned16(yg_parts))
+        return MOE_ERR_INVALID_ARG;
+    if (moe_ffn_stream_parts(W->d, W->f) > max_parts) return MOE_ERR_INVALID_ARG;
+    if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
+    if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, act_dtype))
+        return MOE_ERR_WORKSPACE;
+    return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg_parts, n_parts,
+                                 (hipStream_t)stream);
+}
+
+int moe_combine_parts(const float* yg_parts, int n_parts, const int32_t* inv_perm,
+                      const float* weights, int T, int k, int d, float* y, int residual,
+                      float* yg, void* stream) {
+    if (T < 0 || k < 1 || k > MOE_MAX_K || (long long)T * k >= MOE_MAX_N || !dims_ok(d) ||
+        n_parts < 1 || n_parts > 1024)
+        return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!yg_parts || !inv_perm || !weights || !y) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(yg_parts) || !moe_aligned16(y) || (yg && !moe_aligned16(yg)))
+        return MOE_ERR_INVALID_ARG;
+    const size_t slab = (size_t)T * k * d * sizeof(float);
+    if (ranges_overlap(y, (size_t)T * d * sizeof(float), yg_parts, slab * n_parts) ||
+        ranges_overlap(yg, slab, yg_parts, slab * n_parts))
+        return MOE_ERR_INVALID_ARG;
+    return moe_combine_parts_launch(yg_parts, n_parts, (size_t)T * k * d, inv_perm, weights, T, k, d,
+                                    y, residual != 0, yg, (hipStream_t)stream);
+}
+
+int moe_decode_layer(const moe_weights_t* W, const float* x, const float* logits, int T, int k,
+                     int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
+                     int32_t* perm, int32_t* inv_perm, float* xg, void* workspace,
+                     size_t workspace_bytes, float* yg, float* y, void* stream) {
+    if (!W) return MOE_ERR_INVALID_ARG;
+    if (!tek_ok(T, W->E, k)) return MOE_ERR_INVALID_ARG;
+    if (!x || !logits || !idx || !weights || !counts || !offsets || !perm || !inv_perm || !y)
+        return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(x) || !moe_aligned16(y) || !moe_aligned16(logits) || !moe_aligned16(idx) ||
+        !moe_aligned16(weights) || (xg && !moe_aligned16(xg)) || (yg && !moe_aligned16(yg)))
+        return MOE_ERR_INVALID_ARG;
+    if (W->dtype != MOE_BF16 || !moe_ffn_stream_decode_supported(T, W->E, k, W->d, W->f))
+        return MOE_ERR_UNSUPPORTED;
+    const int N = T * k;
+    if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
+    if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, MOE_F32))
+        return MOE_ERR_WORKSPACE;
+    // every workgroup of the first kernel reads x and logits while one writes the outputs
+    const size_t xb = (size_t)T * W->d * sizeof(float), nb = (size_t)N * W->d * sizeof(float);
+    if (ranges_overlap(x, xb, xg, nb) || ranges_overlap(x, xb, y, xb) ||
+        ranges_overlap(logits, (size_t)T * W->E * 4, weights, (size_t)N * 4))
+        return MOE_ERR_INVALID_ARG;
+    const float* parts = nullptr;
+    int n_parts = 1;
+    size_t stride = 0;
+    int rc = moe_ffn_stream_decode_launch(W, x, logits, T, k, idx, weights, counts, offsets, perm,
+                                          inv_perm, xg, workspace, &parts, &n_parts, &stride,
+                                          (hipStream_t)stream);
+    if (rc != MOE_OK) return rc;
+    return moe_combine_parts_launch(parts, n_parts, stride, inv_perm, weights, T, k, W->d, y, false,
+                                    yg, (hipStream_t)stream);
 }
 
 int moe_combine(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
@@ -193,10 +292,12 @@ int moe_route_permute(const float* logits, int T, int E, int k, const float* x, 
     if (!logits || !x || !idx || !weights || !counts || !offsets || !perm || !inv_perm || !xg)
         return MOE_ERR_INVALID_ARG;
     if (!moe_aligned16(x) || !moe_aligned16(xg)) return MOE_ERR_INVALID_ARG;
+    if (ranges_overlap(x, (size_t)T * d * sizeof(float), xg, (size_t)T * k * d * sizeof(float)))
+        return MOE_ERR_INVALID_ARG;
     if (T < 1 || T > 16 || E > 16) return MOE_ERR_UNSUPPORTED;
     return moe_gate_small_launch(false, x, nullptr, logits, T, d, E, k, 0.f, nullptr, nullptr, idx,
-                                 weights, counts, offsets, perm, inv_perm, xg, nullptr, nullptr, nullptr,
-                                 0, nullptr, (hipStream_t)stream);
+                                 weights, counts, offsets, perm, inv_perm, xg, nullptr, 1, nullptr,
+                                 nullptr, 0, nullptr, (hipStream_t)stream);
 }
 
 int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, int E, int k,
@@ -207,14 +308,20 @@ int moe_norm_route_permute(const float* x, const float* w_gate, int T, int d, in
     if (!x || !w_gate || !h || !logits || !idx || !weights || !counts || !offsets || !perm ||
         !inv_perm || !xg)
         return MOE_ERR_INVALID_ARG;
-    if (!moe_aligned16(x) || !moe_aligned16(xg) || !moe_aligned16(h)) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(x) || !moe_aligned16(xg) || !moe_aligned16(h) || !moe_aligned16(w_gate))
+        return MOE_ERR_INVALID_ARG;
+    // every workgroup reads x while workgroup 0 writes h and the workgroups share xg
+    const size_t xb = (size_t)T * d * sizeof(float);
+    if (ranges_overlap(x, xb, h, xb) || ranges_overlap(x, xb, xg, xb * k))
+        return MOE_ERR_INVALID_ARG;
     if (T < 1 || T > 4 || E > 16) return MOE_ERR_UNSUPPORTED;
     return moe_gate_small_launch(true, x, w_gate, nullptr, T, d, E, k, eps, h, logits, idx, weights,
-                                 counts, offsets, perm, inv_perm, xg, nullptr, nullptr, nullptr, 0,
+                                 counts, offsets, perm, inv_perm, xg, nullptr, 1, nullptr, nullptr, 0,
                                  nullptr, (hipStream_t)stream);
 }
 
-int moe_combine_norm_route_permute(const float* yg_prev, const int32_t* inv_perm_prev,
+int moe_combine_norm_route_permute(const float* yg_prev, int n_parts_prev,
+                                   const int32_t* inv_perm_prev,
                                    const float* weights_prev, int k_prev, const float* x_in,
                                    float* x_out, const float* w_gate, int T, int d, int E, int k,
                                    float eps, float* h, float* logits, int32_t* idx, float* weights,
@@ -226,15 +333,21 @@ int moe_combine_norm_route_permute(const float* yg_prev, const int32_t* inv_perm
         !idx || !weights || !counts || !offsets || !perm || !inv_perm || !xg)
         return MOE_ERR_INVALID_ARG;
     if (!moe_aligned16(x_in) || !moe_aligned16(x_out) || !moe_aligned16(xg) || !moe_aligned16(h) ||
-        !moe_aligned16(yg_prev))
+        !moe_aligned16(yg_prev) || !moe_aligned16(w_gate))
         return MOE_ERR_INVALID_ARG;
+    if (n_parts_prev < 1) return MOE_ERR_INVALID_ARG;
     // every workgroup reads the inputs while workgroup 0 writes the outputs
-    if (x_out == x_in || (const int32_t*)inv_perm == inv_perm_prev ||
-        (const float*)weights == weights_prev || (const float*)xg == yg_prev)
+    const size_t xb = (size_t)T * d * sizeof(float);
+    const size_t ygb = xb * k_prev * n_parts_prev;
+    if (ranges_overlap(x_in, xb, x_out, xb) || ranges_overlap(x_in, xb, h, xb) ||
+        ranges_overlap(x_in, xb, xg, xb * k) || ranges_overlap(yg_prev, ygb, xg, xb * k) ||
+        ranges_overlap(yg_prev, ygb, h, xb) || ranges_overlap(yg_prev, ygb, x_out, xb) ||
+        ranges_overlap(inv_perm_prev, (size_t)T * k_prev * 4, inv_perm, (size_t)T * k * 4) ||
+        ranges_overlap(weights_prev, (size_t)T * k_prev * 4, weights, (size_t)T * k * 4))
         return MOE_ERR_INVALID_ARG;
     if (T < 1 || T > 4 || E > 16) return MOE_ERR_UNSUPPORTED;
     return moe_gate_small_launch(true, x_in, w_gate, nullptr, T, d, E, k, eps, h, logits, idx,
-                                 weights, counts, offsets, perm, inv_perm, xg, yg_prev,
+                                 weights, counts, offsets, perm, inv_perm, xg, yg_prev, n_parts_prev,
                                  inv_perm_prev, weights_prev, k_prev, x_out, (hipStream_t)stream);
 }
 

@@ -39,6 +39,8 @@
 //   * tiles are walked in an order that keeps a weight tile on one XCD (one L2):
 //     expert, then feature tile, then token tile, one contiguous eighth of that
 //     order per XCD.
+#include <atomic>
+
 #include "moe_internal.h"
 #include "moe_frag_pack.h"
 
@@ -707,19 +709,17 @@ static int gg_launch_projection(GroupedArgs& a, GgVariant v, unsigned pgrid, hip
     return MOE_OK;
 }
 
-int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                           const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
-    const int d = W->d, f = W->f, E = W->E;
+// Variant of each projection by the mean number of rows per expert (the host never sees the
+// real counts): up to GG_WIDE_MAX_ROWS the 128-token x 512-feature tile (needs f % 256 == 0
+// for the first projection, d % 512 == 0 for the second; each falls back on its own), up to
+// GG_R192_MAX_ROWS the 192-token x 256-feature one, above that 256 x 256.
+static bool gg_choose(int N, int E, int d, int f, GgVariant& vu, GgVariant& vd) {
     // up tile = 16 fragment rows = 8 column blocks x (w1,w3): f % 128 == 0;
     // down tile = 256 features: d % 256 == 0; both give reductions of >= 8 steps, step
     // counts that are multiples of 4.
-    if (f % 128 != 0 || d % 256 != 0) return MOE_ERR_UNSUPPORTED;
-    // Variant by the mean number of rows per expert (the host never sees the real counts):
-    // up to GG_WIDE_MAX_ROWS the 128-token x 512-feature tile (needs f % 256 == 0 for the
-    // first projection, d % 512 == 0 for the second; each falls back on its own), up to
-    // GG_R192_MAX_ROWS the 192-token x 256-feature one, above that 256 x 256.
+    if (f % 128 != 0 || d % 256 != 0) return false;
     const long long mean_rows = ((long long)N + E - 1) / E;
-    GgVariant vu = GG_STD, vd = GG_STD;
+    vu = vd = GG_STD;
     if (mean_rows <= GG_WIDE_MAX_ROWS) {
         if (f % 256 == 0) vu = GG_WIDE;
         if (d % 512 == 0) vd = GG_WIDE;
@@ -734,14 +734,35 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     };
     if (!fits(vu, d / 32)) vu = GG_STD;
     if (!fits(vd, f / 32)) vd = GG_STD;
-    if (!fits(vu, d / 32) || !fits(vd, f / 32)) return MOE_ERR_UNSUPPORTED;
+    return fits(vu, d / 32) && fits(vd, f / 32);
+}
+
+int moe_ffn_grouped_plan(int N, int E, int d, int f, moe_ffn_plan_t* plan) {
+    GgVariant vu, vd;
+    if (!gg_choose(N, E, d, f, vu, vd)) return MOE_ERR_UNSUPPORTED;
+    const GgShape su = gg_shape(vu), sd = gg_shape(vd);
+    plan->up_tile_rows = 16 * su.tb;
+    plan->up_tile_features = 16 * su.frows;
+    plan->down_tile_rows = 16 * sd.tb;
+    plan->down_tile_features = 16 * sd.frows;
+    return MOE_OK;
+}
+
+int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
+                           const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
+    const int d = W->d, f = W->f, E = W->E;
+    GgVariant vu, vd;
+    if (!gg_choose(N, E, d, f, vu, vd)) return MOE_ERR_UNSUPPORTED;
     const size_t nb = gg_max_blocks(N, E);
     u32x4_t* xp = (u32x4_t*)ws;
     u32x4_t* hp = (u32x4_t*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2));
     const unsigned pgrid = (unsigned)((moe_num_cus() + 7) / 8 * 8);  // persistent: one per CU
 
-    static bool attr_set = false;
-    if (!attr_set) {
+    // once per device; threads that race here set the same attributes
+    static std::atomic<int> attr_set[MOE_MAX_DEVICES];
+    const int dev = moe_current_device();
+    if (dev < 0) return MOE_ERR_HIP;
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
         for (int v = 0; v < GG_NVARIANTS; v++) {
             const GgShape sh = gg_shape((GgVariant)v);
             const void* all[3] = {gg_kernel_ptr<true, 1>((GgVariant)v), gg_kernel_ptr<true, 2>((GgVariant)v),
@@ -750,7 +771,7 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
                 MOE_HIP_TRY(hipFuncSetAttribute(all[i], hipFuncAttributeMaxDynamicSharedMemorySize,
                                                 (int)((size_t)sh.ns * sh.tb * MOE_FRAG_BYTES)));
         }
-        attr_set = true;
+        attr_set[dev].store(1, std::memory_order_release);
     }
 
     if (act_dtype == MOE_BF16)

@@ -27,6 +27,8 @@
 // A workgroup that covers only a piece of a unit's reduction stores its partial sums and
 // mid_fixup_kernel adds the pieces of the unit in workgroup order (deterministic, no
 // atomics) and finishes it.
+#include <atomic>
+
 #include "moe_internal.h"
 #include "moe_frag_pack.h"
 
@@ -430,13 +432,16 @@ int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dty
     const size_t lds_bytes = (size_t)2 * MD_MAX_RB * MD_KC * MOE_FRAG_BYTES;  // 96 KiB
     const unsigned grid = (unsigned)moe_num_cus();
 
-    static bool attr_set = false;
-    if (!attr_set) {
+    // once per device; threads that race here set the same attributes
+    static std::atomic<int> attr_set[MOE_MAX_DEVICES];
+    const int dev = moe_current_device();
+    if (dev < 0) return MOE_ERR_HIP;
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
         MOE_HIP_TRY(hipFuncSetAttribute((const void*)mid_kernel<true>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         MOE_HIP_TRY(hipFuncSetAttribute((const void*)mid_kernel<false>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        attr_set = true;
+        attr_set[dev].store(1, std::memory_order_release);
     }
 
     if (act_dtype == MOE_BF16)

@@ -21,9 +21,18 @@
 // equal ranges so that every workgroup streams the same number of bytes.
 //   up   (x.w1, x.w3 -> silu*mul -> h): one part (the nonlinearity needs the
 //        full sum), 8 waves x d/256 reduction steps.
-//   down (h.w2 -> yg): the long reduction over f is cut into P parts that are
-//        summed into yg with fp32 atomics (yg is zeroed by the up kernel).
+//   down (h.w2 -> yg): the long reduction over f is cut into P parts; every part stores
+//        its partial sums into its own slab [part][N][d] and a small kernel (or the
+//        consumer: the gate-weighted combine) adds the slabs in part order, so the result
+//        does not depend on the order in which workgroups finish.
+// The first-projection kernel can also run the gating function and the per-expert batching
+// of a decode step (T <= 16 tokens, at most 64 slots) in its own prologue, every wave for
+// itself, and then reads the activations straight from the token rows: one launch less and
+// no gathered copy (moe_decode_layer).
+#include <atomic>
+
 #include "moe_internal.h"
+#include "moe_gate_wave.h"
 
 #define ST_MAX_TILES 128
 #define ST_MAX_WAVES 8
@@ -32,24 +41,37 @@ struct StreamArgs {
     const u32x4_t* wfrag;  // fragment-ordered weights
     const void* act;       // [N,K] fp32 or bf16
     const int32_t* offsets;
-    float* out;       // up: h [N,C]; down: yg [N,C]
-    float* zero_ptr;  // buffer zero-filled by this launch (or null)
-    size_t zero_n4;   // its size in float4
+    float* out;       // up: h [N,C]; down: yg [N,C] (P == 1) or the slabs [P][N][C]
+    size_t part_stride;  // floats between two slabs of `out` (0 when P == 1)
     int E, N, K, C;
     int NB;  // C / 16
     int KS;  // K / 32
     int P;   // reduction parts per unit row
     int W;   // waves per workgroup
+    // gating in the prologue (GATE instantiations only): act = x [T,K], offsets unused
+    const float* logits;  // [T,E]
+    int T, k;
+    int32_t* idx;         // [T,k]   written by workgroup 0
+    float* weights;       // [T,k]
+    int32_t* counts;      // [E]
+    int32_t* offsets_out; // [E+1]
+    int32_t* perm;        // [T*k]
+    int32_t* inv_perm;    // [T*k]
+    float* xg;            // [T*k,K] gathered rows, or null (the kernel itself does not need them)
 };
 
+// rowmap (LDS, or null): source row of sorted row i -- the kernels that route in their own
+// prologue read the token rows directly.
 template <int KSW, bool ACT_BF16>
 __device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 1 : 2],
                                                 const void* actp, int K, int row0, int rows,
-                                                int ks0, int lane) {
+                                                int ks0, int lane, const int* rowmap) {
     const int t = lane & 15, kq = lane >> 4;
+    int src_row = row0 + t;
+    if (rowmap && t < rows) src_row = rowmap[row0 + t];
 #pragma unroll
     for (int s = 0; s < KSW; s++) {
-        const size_t off = (size_t)(row0 + t) * K + (size_t)(ks0 + s) * 32 + kq * 8;
+        const size_t off = (size_t)src_row * K + (size_t)(ks0 + s) * 32 + kq * 8;
         if (ACT_BF16) {
             u32x4_t v = {0u, 0u, 0u, 0u};
             if (t < rows) v = *(const u32x4_t*)((const uint16_t*)actp + off);
@@ -82,14 +104,11 @@ __device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 
 // row range, a wave scan numbers the tiles, and the lane writes its experts' tiles into the
 // wave's own copy of the list in LDS.  No workgroup barrier and no serial walk: the list is
 // ready one global-load latency after the kernel starts.  Returns the number of tiles.
+// lo, hi: lane e's row range [offsets[e], offsets[e+1]) (anything for lanes >= E).
 template <int TR, int MAXT>
-__device__ __forceinline__ int stream_tile_list(const int32_t* offsets, int E, int N, int lane,
-                                                int* te, int* tr0, int* trn) {
-    int lo = 0, hi = 0;
-    if (lane < E) {
-        lo = offsets[lane];
-        hi = offsets[lane + 1];
-    }
+__device__ __forceinline__ int stream_tile_list(int lo, int hi, int E, int N, int lane, int* te,
+                                                int* tr0, int* trn) {
+    if (lane >= E) lo = hi = 0;
     lo = lo < 0 ? 0 : (lo > N ? N : lo);
     hi = hi < lo ? lo : (hi > N ? N : hi);
     const int nt = (hi - lo + TR - 1) / TR;
@@ -115,33 +134,70 @@ __device__ __forceinline__ int stream_tile_list(const int32_t* offsets, int E, i
     return __builtin_amdgcn_readfirstlane(total < MAXT ? total : MAXT);
 }
 
-template <int KSW, int NMAT, bool ACT_BF16>
+constexpr int stream_ring_depth(int nl) {
+    int r = nl < 16 ? nl : 16;
+    while (nl % r) --r;
+    return r;
+}
+
+template <int KSW, int NMAT, bool ACT_BF16, bool GATE>
 __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
+    static_assert(!GATE || (NMAT == 2 && !ACT_BF16), "gating runs in the first projection on fp32 rows");
     constexpr int TERMS = ACT_BF16 ? 1 : 2;
     constexpr int NL = KSW * NMAT;         // fragment loads per unit per wave
-    constexpr int R = NL < 16 ? NL : 16;   // loads kept in flight per wave
+    // Loads kept in flight per wave: the largest divisor of NL up to 16.  Load j of a unit
+    // sits in ring slot j % R, and the next unit's load j is requested into the slot of this
+    // unit's load j + NL - R; the two agree only when R divides NL.
+    constexpr int R = stream_ring_depth(NL);
+    static_assert(R >= 1 && R <= 16 && NL % R == 0, "the ring depth must divide the loads per unit");
     __shared__ int s_tiles[ST_MAX_WAVES][3][ST_MAX_TILES];  // per wave: expert, first row, rows
     __shared__ f32x4_t s_red[2][ST_MAX_WAVES][NMAT][64];
+    // per wave (GATE): expert id of every slot, its sorted position, source token of every
+    // sorted row
+    __shared__ int s_gate[GATE ? ST_MAX_WAVES : 1][3][GATE_WAVE_MAX_N];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // The zero fill of the other projection's output runs last: stores pending next to
-    // loads would turn the waits for the first loads into waits for everything.
-    auto zero_fill = [&]() {
-        if (a.zero_ptr) {
-            float4* z = (float4*)a.zero_ptr;
-            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (size_t i = (size_t)blockIdx.x * blockDim.x + tid; i < a.zero_n4;
-                 i += (size_t)gridDim.x * blockDim.x)
-                z[i] = zero;
-        }
-    };
     int* s_te = s_tiles[wave][0];
     int* s_tr0 = s_tiles[wave][1];
     int* s_trn = s_tiles[wave][2];
-    const int n_tiles =
-        stream_tile_list<16, ST_MAX_TILES>(a.offsets, a.E, a.N, lane, s_te, s_tr0, s_trn);
+    int lo = 0, hi = 0;
+    const int* rowmap = nullptr;
+    if (GATE) {
+        // gating function and per-expert batching (Sec. 3.3 "Execution"; Algorithm 1's
+        // inp_size), every wave for itself: no workgroup barrier before the first weight
+        // request.  Wave 0 of workgroup 0 writes the index outputs.
+        int* s_idx = s_gate[wave][0];
+        int* s_pos = s_gate[wave][1];
+        int* s_src = s_gate[wave][2];
+        const bool writer = (blockIdx.x == 0 && wave == 0);
+        gate_route_wave(a.logits, a.T, a.E, a.k, lane, s_idx, writer, a.idx, a.weights);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int off = permute_indices_wave(s_idx, a.N, a.E, a.counts, a.offsets_out, a.perm,
+                                             a.inv_perm, writer, s_pos);
+        if (lane < a.N) s_src[s_pos[lane]] = lane / a.k;
+        lo = off;
+        hi = __shfl_down(off, 1, 64);
+        rowmap = s_src;
+    } else if (lane < a.E) {
+        lo = a.offsets[lane];
+        hi = a.offsets[lane + 1];
+    }
+    // The gathered rows, when the caller wants them, are written last: stores pending next
+    // to loads would turn the waits for the first loads into waits for everything.
+    auto write_xg = [&]() {
+        if (GATE && a.xg) {
+            const int chunks = a.K / 4;
+            for (int i = blockIdx.x; i < a.N; i += gridDim.x) {
+                const float4* src = (const float4*)((const float*)a.act + (size_t)rowmap[i] * a.K);
+                float4* dst = (float4*)(a.xg + (size_t)i * a.K);
+                for (int c = tid; c < chunks; c += blockDim.x) dst[c] = src[c];
+            }
+        }
+    };
+    const int n_tiles = stream_tile_list<16, ST_MAX_TILES>(lo, hi, a.E, a.N, lane, s_te, s_tr0, s_trn);
     // units of this workgroup: an equal share of tiles x parts x column blocks (the product
     // stays below 2^31, host check)
     const unsigned total = (unsigned)n_tiles * (unsigned)a.P * (unsigned)a.NB;
@@ -149,7 +205,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
     const unsigned u_begin = per * blockIdx.x + rem * blockIdx.x / gridDim.x;
     const unsigned u_end = per * (blockIdx.x + 1) + rem * (blockIdx.x + 1) / gridDim.x;
     if (u_begin >= u_end) {  // uniform over the workgroup
-        zero_fill();
+        write_xg();
         return;
     }
 
@@ -182,7 +238,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
         const int row0 = s_tr0[tile], rows = s_trn[tile];
         if (tile != cur_tile || part != cur_part) {
             stream_load_act<KSW, ACT_BF16>(act, a.act, a.K, row0, rows, part * part_ks + wave_ks,
-                                           lane);
+                                           lane, rowmap);
             cur_tile = tile;
             cur_part = part;
         }
@@ -226,7 +282,8 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
             }
             const int t = lane & 15;
             if (t < rows) {
-                float* dst = a.out + (size_t)(row0 + t) * a.C + nb * 16 + 4 * (lane >> 4);
+                float* dst = a.out + (size_t)part * a.part_stride + (size_t)(row0 + t) * a.C +
+                             nb * 16 + 4 * (lane >> 4);
                 if (NMAT == 2) {
                     float4 h;
                     h.x = sa[0] / (1.0f + __expf(-sa[0])) * sb[0];
@@ -234,13 +291,8 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
                     h.z = sa[2] / (1.0f + __expf(-sa[2])) * sb[2];
                     h.w = sa[3] / (1.0f + __expf(-sa[3])) * sb[3];
                     *(float4*)dst = h;
-                } else if (a.P == 1) {
-                    *(float4*)dst = make_float4(sa[0], sa[1], sa[2], sa[3]);
                 } else {
-                    unsafeAtomicAdd(dst + 0, sa[0]);
-                    unsafeAtomicAdd(dst + 1, sa[1]);
-                    unsafeAtomicAdd(dst + 2, sa[2]);
-                    unsafeAtomicAdd(dst + 3, sa[3]);
+                    *(float4*)dst = make_float4(sa[0], sa[1], sa[2], sa[3]);
                 }
             }
         }
@@ -249,7 +301,21 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
         part = npart;
         nb = nnb;
     }
-    zero_fill();
+    write_xg();
+}
+
+// yg = slab 0 + slab 1 + ... in that order (the second projection's reduction parts).
+__global__ __launch_bounds__(256) void stream_reduce_kernel(const float4* __restrict__ part,
+                                                            size_t n4, int P,
+                                                            float4* __restrict__ yg) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        float4 s = part[i];
+        for (int p = 1; p < P; p++) {
+            const float4 v = part[(size_t)p * n4 + i];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        yg[i] = s;
+    }
 }
 
 // Split a reduction of KS steps (of 32) into P parts x W waves x KSW steps.
@@ -273,39 +339,59 @@ static bool stream_pick(int KS, bool allow_parts, int& W, int& KSW, int& P) {
     return best >= 0;
 }
 
-bool moe_ffn_stream_supported(int d, int f) {
-    int W, KSW, P;
-    return stream_pick(d / 32, false, W, KSW, P) && stream_pick(f / 32, true, W, KSW, P);
+struct StreamPlan {
+    int Wu, KSWu;      // first projection: waves, reduction steps per wave (one part)
+    int Wd, KSWd, Pd;  // second projection: waves, steps per wave, reduction parts
+};
+
+static bool stream_plan(int d, int f, StreamPlan& pl) {
+    int Pu;
+    return stream_pick(d / 32, false, pl.Wu, pl.KSWu, Pu) &&
+           stream_pick(f / 32, true, pl.Wd, pl.KSWd, pl.Pd);
 }
 
+bool moe_ffn_stream_supported(int d, int f) {
+    StreamPlan pl;
+    return stream_plan(d, f, pl);
+}
+
+static inline size_t st_align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// h [N,f] fp32, then the second projection's slabs [Pd][N,d] fp32
 size_t moe_ffn_stream_workspace(int N, int E, int d, int f) {
     (void)E;
-    (void)d;
-    return (size_t)N * f * sizeof(float);
+    StreamPlan pl;
+    size_t need = st_align256((size_t)N * f * sizeof(float));
+    if (stream_plan(d, f, pl)) need += (size_t)pl.Pd * N * d * sizeof(float);
+    return need;
 }
 
 // Launches the instantiation for KSW with as many workgroups per CU as fit (kernels with
 // short per-wave reductions use few registers; several resident workgroups then keep
 // enough loads in flight per CU).  The work ranges are equal whatever the grid size.
-template <int NMAT, bool ACT_BF16>
+template <int NMAT, bool ACT_BF16, bool GATE>
 static int stream_dispatch(int KSW, int waves, hipStream_t s, const StreamArgs& a) {
     const void* fn = nullptr;
     int slot = 0;
     switch (KSW) {
-        case 1: fn = (const void*)stream_kernel<1, NMAT, ACT_BF16>; slot = 0; break;
-        case 2: fn = (const void*)stream_kernel<2, NMAT, ACT_BF16>; slot = 1; break;
-        case 4: fn = (const void*)stream_kernel<4, NMAT, ACT_BF16>; slot = 2; break;
-        case 8: fn = (const void*)stream_kernel<8, NMAT, ACT_BF16>; slot = 3; break;
-        case 16: fn = (const void*)stream_kernel<16, NMAT, ACT_BF16>; slot = 4; break;
-        case 10: fn = (const void*)stream_kernel<10, NMAT, ACT_BF16>; slot = 5; break;
+        case 1: fn = (const void*)stream_kernel<1, NMAT, ACT_BF16, GATE>; slot = 0; break;
+        case 2: fn = (const void*)stream_kernel<2, NMAT, ACT_BF16, GATE>; slot = 1; break;
+        case 4: fn = (const void*)stream_kernel<4, NMAT, ACT_BF16, GATE>; slot = 2; break;
+        case 8: fn = (const void*)stream_kernel<8, NMAT, ACT_BF16, GATE>; slot = 3; break;
+        case 16: fn = (const void*)stream_kernel<16, NMAT, ACT_BF16, GATE>; slot = 4; break;
+        case 10: fn = (const void*)stream_kernel<10, NMAT, ACT_BF16, GATE>; slot = 5; break;
         default: return MOE_ERR_UNSUPPORTED;
     }
-    static int occ_cache[6][ST_MAX_WAVES + 1];  // per instantiation: 0 = not asked yet
-    int occ = occ_cache[slot][waves];
+    // per device and instantiation: 0 = not asked yet.  Threads that race here ask the
+    // same question and store the same answer.
+    static std::atomic<int> occ_cache[MOE_MAX_DEVICES][6][ST_MAX_WAVES + 1];
+    const int dev = moe_current_device();
+    if (dev < 0) return MOE_ERR_HIP;
+    int occ = occ_cache[dev][slot][waves].load(std::memory_order_relaxed);
     if (occ == 0) {
         MOE_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, 64 * waves, 0));
         occ = occ < 1 ? 1 : (occ > 4 ? 4 : occ);
-        occ_cache[slot][waves] = occ;
+        occ_cache[dev][slot][waves].store(occ, std::memory_order_relaxed);
     }
     StreamArgs args = a;
     void* params[1] = {(void*)&args};
@@ -314,39 +400,112 @@ static int stream_dispatch(int KSW, int waves, hipStream_t s, const StreamArgs& 
     return moe_launch_status();
 }
 
-int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                          const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
-    const int d = W->d, f = W->f, E = W->E;
-    if (N / 16 + E > ST_MAX_TILES) return MOE_ERR_UNSUPPORTED;
-    int Wu, KSWu, Pu, Wd, KSWd, Pd;
-    if (!stream_pick(d / 32, false, Wu, KSWu, Pu) || !stream_pick(f / 32, true, Wd, KSWd, Pd))
-        return MOE_ERR_UNSUPPORTED;
+static bool stream_shape_ok(const StreamPlan& pl, int N, int E, int d, int f) {
+    if (N / 16 + E > ST_MAX_TILES) return false;
     // unit numbers (tiles x parts x column blocks) are 32-bit in the kernels
-    if ((long long)ST_MAX_TILES * Pd * ((d > f ? d : f) / 16) >= (1ll << 31))
-        return MOE_ERR_UNSUPPORTED;
-    float* h = (float*)ws;
-    StreamArgs up;
+    return (long long)ST_MAX_TILES * pl.Pd * ((d > f ? d : f) / 16) < (1ll << 31);
+}
+
+static StreamArgs stream_args_up(const moe_weights* W, const StreamPlan& pl, const void* act,
+                                 const int32_t* offsets, int N, float* h) {
+    StreamArgs up = {};
     up.wfrag = (const u32x4_t*)W->w13;
-    up.act = xg;
+    up.act = act;
     up.offsets = offsets;
     up.out = h;
-    up.zero_ptr = (Pd > 1) ? yg : nullptr;
-    up.zero_n4 = (size_t)N * d / 4;
-    up.E = E; up.N = N; up.K = d; up.C = f;
-    up.NB = f / 16; up.KS = d / 32; up.P = 1; up.W = Wu;
-    int rc = (act_dtype == MOE_BF16) ? stream_dispatch<2, true>(KSWu, Wu, s, up)
-                                     : stream_dispatch<2, false>(KSWu, Wu, s, up);
-    if (rc != MOE_OK) return rc;
-    moe_record_mid_event(s);
+    up.part_stride = 0;
+    up.E = W->E; up.N = N; up.K = W->d; up.C = W->f;
+    up.NB = W->f / 16; up.KS = W->d / 32; up.P = 1; up.W = pl.Wu;
+    return up;
+}
 
-    StreamArgs dn;
+// out: yg itself when there is one part, else the slabs
+static StreamArgs stream_args_down(const moe_weights* W, const StreamPlan& pl, const float* h,
+                                   const int32_t* offsets, int N, float* out) {
+    StreamArgs dn = {};
     dn.wfrag = (const u32x4_t*)W->w2;
     dn.act = h;
     dn.offsets = offsets;
-    dn.out = yg;
-    dn.zero_ptr = nullptr;
-    dn.zero_n4 = 0;
-    dn.E = E; dn.N = N; dn.K = f; dn.C = d;
-    dn.NB = d / 16; dn.KS = f / 32; dn.P = Pd; dn.W = Wd;
-    return stream_dispatch<1, false>(KSWd, Wd, s, dn);
+    dn.out = out;
+    dn.part_stride = pl.Pd > 1 ? (size_t)N * W->d : 0;
+    dn.E = W->E; dn.N = N; dn.K = W->f; dn.C = W->d;
+    dn.NB = W->d / 16; dn.KS = W->f / 32; dn.P = pl.Pd; dn.W = pl.Wd;
+    return dn;
+}
+
+int moe_ffn_stream_parts(int d, int f) {
+    StreamPlan pl;
+    return stream_plan(d, f, pl) ? pl.Pd : 0;
+}
+
+// n_parts == null: `out` is yg [N,d]; the slabs of a split reduction go to the workspace and
+// are added by a third launch.  Else `out` holds moe_ffn_stream_parts(d, f) slabs [N,d] that
+// are left for the caller to add, and *n_parts receives their number.
+int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
+                          const int32_t* offsets, int N, void* ws, float* out, int* n_parts,
+                          hipStream_t s) {
+    const int d = W->d, f = W->f, E = W->E;
+    StreamPlan pl;
+    if (!stream_plan(d, f, pl) || !stream_shape_ok(pl, N, E, d, f)) return MOE_ERR_UNSUPPORTED;
+    float* h = (float*)ws;
+    float* slabs = n_parts ? out
+                           : (float*)((unsigned char*)ws + st_align256((size_t)N * f * sizeof(float)));
+    const StreamArgs up = stream_args_up(W, pl, xg, offsets, N, h);
+    int rc = (act_dtype == MOE_BF16) ? stream_dispatch<2, true, false>(pl.KSWu, pl.Wu, s, up)
+                                     : stream_dispatch<2, false, false>(pl.KSWu, pl.Wu, s, up);
+    if (rc != MOE_OK) return rc;
+    moe_record_mid_event(s);
+    const StreamArgs dn = stream_args_down(W, pl, h, offsets, N, pl.Pd > 1 ? slabs : out);
+    rc = stream_dispatch<1, false, false>(pl.KSWd, pl.Wd, s, dn);
+    if (n_parts) *n_parts = pl.Pd;
+    if (rc != MOE_OK || pl.Pd == 1 || n_parts) return rc;
+    const size_t n4 = (size_t)N * d / 4;
+    size_t blocks = (n4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(stream_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                       (const float4*)slabs, n4, pl.Pd, (float4*)out);
+    return moe_launch_status();
+}
+
+bool moe_ffn_stream_decode_supported(int T, int E, int k, int d, int f) {
+    StreamPlan pl;
+    return T >= 1 && T <= 16 && E <= GATE_WAVE_MAX_E && T * k <= GATE_WAVE_MAX_N &&
+           stream_plan(d, f, pl) && stream_shape_ok(pl, T * k, E, d, f);
+}
+
+// Both projections of a decode step with the gating function and the per-expert batching in
+// the first kernel's prologue.  The second projection's result stays in *n_parts slabs of
+// [T*k, d] floats at *parts, *part_stride floats apart, for the caller's combine to add.
+int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const float* logits, int T,
+                                 int k, int32_t* idx, float* weights, int32_t* counts,
+                                 int32_t* offsets, int32_t* perm, int32_t* inv_perm, float* xg,
+                                 void* ws, const float** parts, int* n_parts, size_t* part_stride,
+                                 hipStream_t s) {
+    const int d = W->d, f = W->f, E = W->E, N = T * k;
+    StreamPlan pl;
+    if (!moe_ffn_stream_decode_supported(T, E, k, d, f) || !stream_plan(d, f, pl))
+        return MOE_ERR_UNSUPPORTED;
+    float* h = (float*)ws;
+    float* slabs = (float*)((unsigned char*)ws + st_align256((size_t)N * f * sizeof(float)));
+    StreamArgs up = stream_args_up(W, pl, x, nullptr, N, h);
+    up.logits = logits;
+    up.T = T;
+    up.k = k;
+    up.idx = idx;
+    up.weights = weights;
+    up.counts = counts;
+    up.offsets_out = offsets;
+    up.perm = perm;
+    up.inv_perm = inv_perm;
+    up.xg = xg;
+    int rc = stream_dispatch<2, false, true>(pl.KSWu, pl.Wu, s, up);
+    if (rc != MOE_OK) return rc;
+    moe_record_mid_event(s);
+    StreamArgs dn = stream_args_down(W, pl, h, offsets, N, slabs);
+    dn.part_stride = (size_t)N * d;
+    rc = stream_dispatch<1, false, false>(pl.KSWd, pl.Wd, s, dn);
+    *parts = slabs;
+    *n_parts = pl.Pd;
+    *part_stride = (size_t)N * d;
+    return rc;
 }

@@ -11,6 +11,7 @@
 #define MOE_MAX_E 64
 #define MOE_MAX_K 8
 #define MOE_MAX_N (1 << 24)
+#define MOE_MAX_DEVICES 64  // per-device tables of one-time set-up
 
 // bf16 weights are stored in "fragment order": the unit is the operand tile of
 // one v_mfma_f32_16x16x32_bf16 -- 16 output features (rows of W^T) by 32
@@ -50,13 +51,13 @@ static inline int moe_launch_status() {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-// Event recorded between the two projections of moe_expert_ffn (measurement hook), or null.
-extern hipEvent_t g_moe_mid_event;
-static inline void moe_record_mid_event(hipStream_t s) {
-    if (g_moe_mid_event) (void)hipEventRecord(g_moe_mid_event, s);
-}
+// Event recorded between the two projections of moe_expert_ffn (measurement hook of
+// moe_probe.h), or null: one relaxed atomic load per call when it is off.
+void moe_record_mid_event(hipStream_t s);
 
-// Number of compute units of the current device (cached per process; 256 on MI355X).
+// Current device, or -1 (on a HIP error, or an ordinal beyond MOE_MAX_DEVICES).
+int moe_current_device();
+// Number of compute units of the current device (cached per device; 256 on MI355X).
 int moe_num_cus();
 
 // ---- expert FFN kernel families (each returns a moe_status_t) ----------------
@@ -66,10 +67,19 @@ int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* off
 
 bool moe_ffn_stream_supported(int d, int f);
 size_t moe_ffn_stream_workspace(int N, int E, int d, int f);
+int moe_ffn_stream_parts(int d, int f);  // reduction parts of the second projection (0: unsupported)
 int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                          const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
+                          const int32_t* offsets, int N, void* ws, float* out, int* n_parts,
+                          hipStream_t s);
+bool moe_ffn_stream_decode_supported(int T, int E, int k, int d, int f);
+int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const float* logits, int T,
+                                 int k, int32_t* idx, float* weights, int32_t* counts,
+                                 int32_t* offsets, int32_t* perm, int32_t* inv_perm, float* xg,
+                                 void* ws, const float** parts, int* n_parts, size_t* part_stride,
+                                 hipStream_t s);
 
 size_t moe_ffn_grouped_workspace(int N, int E, int d, int f);
+int moe_ffn_grouped_plan(int N, int E, int d, int f, moe_ffn_plan_t* plan);  // fills the tile fields
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
                            const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
 
@@ -119,7 +129,13 @@ int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const 
                           int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
                           int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
                           int32_t* perm, int32_t* inv_perm, float* xg, const float* yg_prev,
-                          const int32_t* inv_perm_prev, const float* weights_prev, int k_prev,
-                          float* x_out, hipStream_t s);
+                          int n_parts_prev, const int32_t* inv_perm_prev, const float* weights_prev,
+                          int k_prev, float* x_out, hipStream_t s);
 int moe_combine_residual_launch(const float* yg, const int32_t* inv_perm, const float* weights, int T,
                                 int k, int d, float* x, hipStream_t s);
+// y[t] = sum_j w[t,j] * (sum_p parts[p][inv_perm[t*k+j]]), parts `part_stride` floats apart;
+// yg_out (or null) receives the summed rows.
+// residual: y[t] += ... instead of y[t] = ...
+int moe_combine_parts_launch(const float* parts, int n_parts, size_t part_stride,
+                             const int32_t* inv_perm, const float* weights, int T, int k, int d,
+                             float* y, bool residual, float* yg_out, hipStream_t s);

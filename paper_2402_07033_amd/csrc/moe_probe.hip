@@ -4,7 +4,23 @@
 // operands are realistic (random) rather than constant?  The published peak
 // assumes the maximum clock; under a matrix-core load the board lowers its
 // clock, and more so when the operand bits toggle.
+#include <atomic>
+
 #include "moe_internal.h"
+#include "moe_probe.h"
+
+// Event recorded between the two projections of moe_expert_ffn, or null.
+static std::atomic<hipEvent_t> g_mid_event{nullptr};
+
+extern "C" int moe_set_ffn_mid_event(void* hip_event) {
+    g_mid_event.store((hipEvent_t)hip_event, std::memory_order_release);
+    return MOE_OK;
+}
+
+void moe_record_mid_event(hipStream_t s) {
+    hipEvent_t ev = g_mid_event.load(std::memory_order_acquire);
+    if (ev) (void)hipEventRecord(ev, s);
+}
 
 // 4 waves per workgroup, 16 accumulators per wave, operands cycle through 8
 // register sets loaded once from `operands` (64 KiB of bf16 bit patterns).

@@ -9,6 +9,7 @@
 //          expert segment is the slot order and the result is unique.
 // combine: y[t] = sum_j w[t,j] * yg[inv_perm[t*k+j]], float4 lanes along d.
 #include "moe_internal.h"
+#include "moe_gate_wave.h"
 
 // ------------------------------------------------------------------ route ----
 
@@ -163,47 +164,6 @@ __device__ void permute_indices(const int32_t* __restrict__ idx, int N, int E,
             if (s_pos) s_pos[p] = pos;
         }
         __syncthreads();
-    }
-}
-
-// The same batching for N <= 64 slots by one wavefront, without workgroup barriers: lane p
-// owns slot p; a ballot per expert gives the expert's count and every lane's rank among
-// the lanes of its expert.  The caller's next barrier publishes s_pos.
-__device__ __forceinline__ void permute_indices_wave(const int* __restrict__ s_idx, int N, int E,
-                                                     int32_t* __restrict__ counts,
-                                                     int32_t* __restrict__ offsets,
-                                                     int32_t* __restrict__ perm,
-                                                     int32_t* __restrict__ inv_perm, bool write,
-                                                     int* s_pos) {
-    const int lane = threadIdx.x & 63;
-    int e = -1;
-    if (lane < N) {
-        e = s_idx[lane];
-        e = e < 0 ? 0 : (e >= E ? E - 1 : e);
-    }
-    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int run = 0, pos = 0, my_cnt = 0, my_off = 0;
-    for (int ee = 0; ee < E; ee++) {
-        const unsigned long long m = __ballot(e == ee);
-        const int c = __popcll(m);
-        if (e == ee) pos = run + __popcll(m & below);
-        if (lane == ee) {
-            my_cnt = c;
-            my_off = run;
-        }
-        run += c;
-    }
-    if (lane == E) my_off = run;
-    if (lane < N) {
-        s_pos[lane] = pos;
-        if (write) {
-            perm[pos] = lane;
-            inv_perm[lane] = pos;
-        }
-    }
-    if (write) {
-        if (lane < E) counts[lane] = my_cnt;
-        if (lane <= E) offsets[lane] = my_off;
     }
 }
 
@@ -409,13 +369,19 @@ int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t 
 //   x[t,r] + sum_j w_prev[t,j] * yg_prev[pos_prev[t,j], r]
 // in the arithmetic of combine_residual_kernel.
 struct GatePrev {
-    const float* yg;   // [N_prev, d] (global)
+    const float* yg;   // [P][N_prev, d] (global): the reduction parts of the block before,
+                       // added in part order (P = 1: its plain output)
     const int* pos;    // [T * k] rows of yg (inv_perm of the block before)
     const float* w;    // [T * k] gate weights of the block before
     int k;
+    int P;
+    size_t pstride;    // floats between two parts
 };
 
-template <int TT, int UNR, int KJMAX, int STRIDE = PERM_THREADS>
+#define GATE_MAX_PARTS 4  // reduction parts of the block before that the seam kernel adds
+
+// PMAX: compile-time bound on pv.P; every part's load is issued before the first is used.
+template <int TT, int UNR, int KJMAX, int PMAX, int STRIDE = PERM_THREADS>
 __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
                                                   const float* __restrict__ w_gate, int T, int d,
                                                   int E, int tid, const GatePrev& pv,
@@ -425,7 +391,7 @@ __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
     constexpr int KJ = COMB ? KJMAX : 1;
     const bool vec = (E & 3) == 0;  // rows of w_gate are then 16-byte aligned
     for (int r0 = tid; r0 < d; r0 += UNR * STRIDE) {
-        float wr[UNR][GATE_MAX_E], xv[UNR][TT], yv[UNR][TT][KJ];
+        float wr[UNR][GATE_MAX_E], xv[UNR][TT], yv[UNR][TT][KJ][PMAX];
 #pragma unroll
         for (int u = 0; u < UNR; u++) {
             const int r = r0 + u * STRIDE;
@@ -435,7 +401,9 @@ __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
             for (int t = 0; t < TT; t++) {
                 xv[u][t] = 0.f;
 #pragma unroll
-                for (int j = 0; j < KJ; j++) yv[u][t][j] = 0.f;
+                for (int j = 0; j < KJ; j++)
+#pragma unroll
+                    for (int q = 0; q < PMAX; q++) yv[u][t][j][q] = 0.f;
             }
             if (r < d) {
                 if (vec) {
@@ -459,7 +427,12 @@ __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
                         if (COMB) {
 #pragma unroll
                             for (int j = 0; j < KJ; j++)
-                                if (j < pv.k) yv[u][t][j] = pv.yg[(size_t)pv.pos[t * pv.k + j] * d + r];
+                                if (j < pv.k) {
+                                    const float* p = pv.yg + (size_t)pv.pos[t * pv.k + j] * d + r;
+#pragma unroll
+                                    for (int q = 0; q < PMAX; q++)
+                                        if (q < pv.P) yv[u][t][j][q] = p[(size_t)q * pv.pstride];
+                                }
                         }
                     }
                 }
@@ -474,7 +447,13 @@ __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
                         float a = 0.f;
 #pragma unroll
                         for (int j = 0; j < KJ; j++)
-                            if (j < pv.k) a += pv.w[t * pv.k + j] * yv[u][t][j];
+                            if (j < pv.k) {
+                                float v = yv[u][t][j][0];  // the parts in part order
+#pragma unroll
+                                for (int q = 1; q < PMAX; q++)
+                                    if (q < pv.P) v += yv[u][t][j][q];
+                                a += pv.w[t * pv.k + j] * v;
+                            }
                         xv[u][t] += a;
                     }
                 }
@@ -493,13 +472,13 @@ __device__ __forceinline__ void gate_partial_sums(const float* __restrict__ x,
 }
 
 
-template <bool NORM, int KJMAX>
+template <bool NORM, int KJMAX, int PMAX>
 __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
     const float* __restrict__ x, const float* __restrict__ w_gate, const float* __restrict__ logits_in,
     int T, int d, int E, int k, float eps, float* __restrict__ h_out, float* __restrict__ logits_out,
     int32_t* __restrict__ idx, float* __restrict__ weights, int32_t* __restrict__ counts,
     int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
-    float* __restrict__ xg, const float* __restrict__ yg_prev,
+    float* __restrict__ xg, const float* __restrict__ yg_prev, int n_parts_prev,
     const int32_t* __restrict__ inv_perm_prev, const float* __restrict__ weights_prev, int k_prev,
     float* __restrict__ x_out) {
     __shared__ int s_ppos[GATE_NORM_MAX_T * MOE_MAX_K];
@@ -519,7 +498,8 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
     // global memory (uniform addresses), so that their other loads need not wait for a
     // barrier; the LDS copies serve the row phase at the end and are published by the
     // barriers in between.
-    GatePrev pv = {yg_prev, inv_perm_prev, weights_prev, k_prev};
+    GatePrev pv = {yg_prev, inv_perm_prev, weights_prev, k_prev, n_parts_prev,
+                   (size_t)T * k_prev * d};
     if (COMB && tid < T * k_prev) {
         s_ppos[tid] = inv_perm_prev[tid];
         s_pw[tid] = weights_prev[tid];
@@ -539,10 +519,11 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
         // are issued before the first use, so a thread pays the memory latency once per
         // group instead of once per row (4 rows per group for one token, else 2).
         if (T == 1)
-            gate_partial_sums<1, (KJMAX > 2 ? 2 : 4), KJMAX>(x, w_gate, T, d, E, tid, pv, ss, acc);
+            gate_partial_sums<1, (KJMAX * PMAX > 2 ? 2 : 4), KJMAX, PMAX>(x, w_gate, T, d, E, tid, pv, ss,
+                                                                          acc);
         else
-            gate_partial_sums<GATE_NORM_MAX_T, (COMB ? 1 : 2), KJMAX>(x, w_gate, T, d, E, tid, pv,
-                                                                       ss, acc);
+            gate_partial_sums<GATE_NORM_MAX_T, (COMB ? 1 : 2), KJMAX, PMAX>(x, w_gate, T, d, E, tid,
+                                                                             pv, ss, acc);
         // wave reduce, then across the 16 waves through LDS
 #pragma unroll
         for (int t = 0; t < GATE_NORM_MAX_T; t++) {
@@ -658,7 +639,17 @@ __global__ __launch_bounds__(PERM_THREADS) void gate_small_kernel(
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int j = 0; j < k_prev; j++) {
                 const float w = s_pw[t * k_prev + j];
-                const float4 v = ((const float4*)(yg_prev + (size_t)s_ppos[t * k_prev + j] * d))[c];
+                const float4* src = (const float4*)(yg_prev + (size_t)s_ppos[t * k_prev + j] * d) + c;
+                float4 pq[PMAX];
+#pragma unroll
+                for (int q = 0; q < PMAX; q++)
+                    if (q < n_parts_prev) pq[q] = src[(size_t)q * (pv.pstride / 4)];
+                float4 v = pq[0];
+#pragma unroll
+                for (int q = 1; q < PMAX; q++)
+                    if (q < n_parts_prev) {
+                        v.x += pq[q].x; v.y += pq[q].y; v.z += pq[q].z; v.w += pq[q].w;
+                    }
                 a.x += w * v.x;
                 a.y += w * v.y;
                 a.z += w * v.z;
@@ -697,21 +688,25 @@ int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const 
                           int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
                           int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
                           int32_t* perm, int32_t* inv_perm, float* xg, const float* yg_prev,
-                          const int32_t* inv_perm_prev, const float* weights_prev, int k_prev,
-                          float* x_out, hipStream_t s) {
+                          int n_parts_prev, const int32_t* inv_perm_prev, const float* weights_prev,
+                          int k_prev, float* x_out, hipStream_t s) {
     const int N = T * k;
     const unsigned grid = (unsigned)(N < 32 ? N : 32);
     const bool comb = (yg_prev != nullptr);
     if (comb && !norm) return MOE_ERR_INVALID_ARG;
-#define GATE_LAUNCH(NORM, KJMAX)                                                                  \
-    hipLaunchKernelGGL((gate_small_kernel<NORM, KJMAX>), dim3(grid), dim3(PERM_THREADS), 0, s, x, \
+    if (comb && (n_parts_prev < 1 || n_parts_prev > GATE_MAX_PARTS)) return MOE_ERR_UNSUPPORTED;
+#define GATE_LAUNCH(NORM, KJMAX, PMAX)                                                            \
+    hipLaunchKernelGGL((gate_small_kernel<NORM, KJMAX, PMAX>), dim3(grid), dim3(PERM_THREADS), 0, \
+                       s, x,                                                                      \
                        w_gate, logits_in, T, d, E, k, eps, h_out, logits_out, idx, weights,      \
-                       counts, offsets, perm, inv_perm, xg, yg_prev, inv_perm_prev,              \
-                       weights_prev, k_prev, x_out)
-    if (comb && k_prev <= 2) GATE_LAUNCH(true, 2);
-    else if (comb) GATE_LAUNCH(true, MOE_MAX_K);
-    else if (norm) GATE_LAUNCH(true, 0);
-    else GATE_LAUNCH(false, 0);
+                       counts, offsets, perm, inv_perm, xg, yg_prev, n_parts_prev,               \
+                       inv_perm_prev, weights_prev, k_prev, x_out)
+    if (comb && k_prev <= 2 && n_parts_prev == 1) GATE_LAUNCH(true, 2, 1);
+    else if (comb && k_prev <= 2) GATE_LAUNCH(true, 2, GATE_MAX_PARTS);
+    else if (comb && n_parts_prev == 1) GATE_LAUNCH(true, MOE_MAX_K, 1);
+    else if (comb) GATE_LAUNCH(true, MOE_MAX_K, GATE_MAX_PARTS);
+    else if (norm) GATE_LAUNCH(true, 0, 1);
+    else GATE_LAUNCH(false, 0, 1);
 #undef GATE_LAUNCH
     return moe_launch_status();
 }
@@ -753,6 +748,65 @@ int moe_combine_residual_launch(const float* yg, const int32_t* inv_perm, const 
     return moe_launch_status();
 }
 
+// ------------------------------------- combine over unsummed reduction parts ----
+// The second projection of the decode kernels leaves its reduction parts as slabs
+// [P][N,d]; this combine adds them in part order while it weights and gathers:
+//   v      = parts[0][pos] + parts[1][pos] + ...          (pos = inv_perm[t*k+j])
+//   y[t]   = (RESID ? y[t] : 0) + sum_j w[t,j] * v
+// and, when asked, stores v as yg[pos] (every row of yg belongs to exactly one slot).
+template <bool RESID>
+__global__ __launch_bounds__(256) void combine_parts_kernel(
+    const float4* __restrict__ parts, int P, size_t stride4, const int32_t* __restrict__ inv_perm,
+    const float* __restrict__ weights, int T, int k, int row_chunks, float4* __restrict__ y,
+    float4* __restrict__ yg_out) {
+    const int t = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T || c >= row_chunks) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; j++) {
+        const float w = weights[(size_t)t * k + j];
+        const size_t row = (size_t)inv_perm[(size_t)t * k + j] * row_chunks + c;
+        float4 v = parts[row];
+        for (int p = 1; p < P; p++) {
+            const float4 u = parts[(size_t)p * stride4 + row];
+            v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+        }
+        if (yg_out) yg_out[row] = v;
+        acc.x += w * v.x;
+        acc.y += w * v.y;
+        acc.z += w * v.z;
+        acc.w += w * v.w;
+    }
+    if (RESID) {
+        float4 r = y[(size_t)t * row_chunks + c];
+        r.x += acc.x; r.y += acc.y; r.z += acc.z; r.w += acc.w;
+        acc = r;
+    }
+    y[(size_t)t * row_chunks + c] = acc;
+}
+
+int moe_combine_parts_launch(const float* parts, int n_parts, size_t part_stride,
+                             const int32_t* inv_perm, const float* weights, int T, int k, int d,
+                             float* y, bool residual, float* yg_out, hipStream_t s) {
+    const int row_chunks = d / 4;
+    dim3 grid((unsigned)((row_chunks + 255) / 256), 1);
+    for (int t0 = 0; t0 < T; t0 += 65535) {
+        const int tn = (T - t0) < 65535 ? (T - t0) : 65535;
+        grid.y = (unsigned)tn;
+        if (residual)
+            hipLaunchKernelGGL(combine_parts_kernel<true>, grid, dim3(256), 0, s, (const float4*)parts,
+                               n_parts, part_stride / 4, inv_perm + (size_t)t0 * k,
+                               weights + (size_t)t0 * k, tn, k, row_chunks,
+                               (float4*)(y + (size_t)t0 * d), (float4*)yg_out);
+        else
+            hipLaunchKernelGGL(combine_parts_kernel<false>, grid, dim3(256), 0, s, (const float4*)parts,
+                               n_parts, part_stride / 4, inv_perm + (size_t)t0 * k,
+                               weights + (size_t)t0 * k, tn, k, row_chunks,
+                               (float4*)(y + (size_t)t0 * d), (float4*)yg_out);
+    }
+    return moe_launch_status();
+}
+
 // ------------------------------- RMSNorm + router logits for any number of tokens ----
 // NL_TOK tokens per workgroup of 1024 threads, so that a row of the router matrix is loaded
 // once for NL_TOK tokens; thread-strided partial sums with grouped loads (see
@@ -780,8 +834,8 @@ __global__ __launch_bounds__(NL_THREADS) void norm_logits_kernel(const float* __
 #pragma unroll
         for (int e = 0; e < GATE_MAX_E; e++) acc[t][e] = 0.f;
     }
-    const GatePrev none = {nullptr, nullptr, nullptr, 0};
-    gate_partial_sums<NL_TOK, 4, 0, NL_THREADS>(xb, w_gate, Tl, d, E, tid, none, ss, acc);
+    const GatePrev none = {nullptr, nullptr, nullptr, 0, 1, 0};
+    gate_partial_sums<NL_TOK, 4, 0, 1, NL_THREADS>(xb, w_gate, Tl, d, E, tid, none, ss, acc);
 #pragma unroll
     for (int t = 0; t < NL_TOK; t++) {
         if (t < Tl) {

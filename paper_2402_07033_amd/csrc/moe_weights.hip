@@ -1,22 +1,34 @@
 // One-time repack of the expert matrices (paper Sec. 3.2: three d x f matrices
 // per expert) into the order the matrix-core kernels stream them.
+#include <atomic>
 #include <new>
 
 #include "moe_internal.h"
 
-static int g_num_cus = 0;
+int moe_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    return (dev >= 0 && dev < MOE_MAX_DEVICES) ? dev : -1;
+}
 
 int moe_num_cus() {
-    if (g_num_cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    // 0 = not asked yet; threads that race here store the same value
+    static std::atomic<int> cus[MOE_MAX_DEVICES];
+    const int dev = moe_current_device();
+    if (dev < 0) return 256;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            n <= 0) {
             (void)hipGetLastError();
             return 256;
         }
-        g_num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
-    return g_num_cus;
+    return n;
 }
 
 // src: [E][K][C] bf16 row-major (reduction index k, output feature c).
@@ -116,10 +128,15 @@ int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E,
 int moe_weights_free_impl(moe_weights* W) {
     if (!W) return MOE_OK;
     int rc = MOE_OK;
+    // the handle's own device: wait for the kernels that may still read the matrices
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    if (have_cur && cur != W->device && hipSetDevice(W->device) != hipSuccess) rc = MOE_ERR_HIP;
     if (hipDeviceSynchronize() != hipSuccess) rc = MOE_ERR_HIP;
     void* p[5] = {W->w13, W->w2, W->w1f, W->w3f, W->w2f};
     for (int i = 0; i < 5; i++)
         if (p[i] && hipFree(p[i]) != hipSuccess) rc = MOE_ERR_HIP;
+    if (have_cur && cur != W->device) (void)hipSetDevice(cur);
     if (rc != MOE_OK) (void)hipGetLastError();
     delete W;
     return rc;

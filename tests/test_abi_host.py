@@ -18,19 +18,24 @@ def L():
     return m.lib()
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+def _declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(L):
-    names = _declared_functions()
-    assert "moe_route" in names and "moe_expert_ffn" in names and len(names) >= 12
-    for n in names:
-        assert hasattr(L, n), f"{n} declared in include/moe.h but not exported"
     from paper_2402_07033_amd import binding
+    names = _declared_functions("moe.h")
+    assert "moe_route" in names and "moe_expert_ffn" in names and len(names) >= 12
+    probes = _declared_functions("moe_probe.h")
+    assert "moe_hbm_read_probe" in probes
+    for n in names + probes:
+        assert hasattr(L, n), f"{n} declared under include/ but not exported"
     assert sorted(binding.EXPORTS) == names
+    assert sorted(binding.PROBE_EXPORTS) == probes
+    # the measurement probes are not declared in the layer's header
+    assert not set(names) & set(probes)
 
 
 def test_status_strings(L):
@@ -68,6 +73,41 @@ def test_argument_errors_return_before_any_launch(L):
     assert L.moe_rmsnorm(p, 2, 100, C.c_float(1e-5), p, None) == INVALID
     assert L.moe_router_logits(p, p, 2, 128, 65, p, None) == INVALID
     assert L.moe_residual_add(None, p, 2, 128, None) == INVALID
+    # fused front ends: an output that overlaps an input every workgroup reads is refused
+    big = (C.c_char * (1 << 16))()
+    q = (C.addressof(big) + 255) & ~255
+    x, h, xg, rest = (C.c_void_p(q + o) for o in (0, 4096, 8192, 32768))
+    args = (2, 256, 8, 2, C.c_float(1e-5))   # T, d, E, k, eps: x is 2 KiB
+    ok_tail = (rest,) * 7
+    assert L.moe_norm_route_permute(x, rest, *args, x, *ok_tail, xg, None) == INVALID   # h == x
+    assert L.moe_norm_route_permute(x, rest, *args, h, *ok_tail, x, None) == INVALID    # xg == x
+    mis_gate = C.c_void_p(rest.value + 4)
+    assert L.moe_norm_route_permute(x, mis_gate, *args, h, *ok_tail, xg, None) == INVALID
+    assert L.moe_route_permute(rest, 2, 8, 2, x, 256, *(rest,) * 6, x, None) == INVALID   # xg == x
+    # seam: x_out == x_in, h == x_in, n_parts < 1
+    seam = lambda xin, xout, hh, parts: L.moe_combine_norm_route_permute(
+        rest, parts, rest, rest, 2, xin, xout, rest, *args, hh, *ok_tail, xg, None)
+    assert seam(x, x, h, 1) == INVALID and seam(x, h, x, 1) == INVALID
+    assert seam(x, C.c_void_p(q + 16384), h, 0) == INVALID
+    # combine over parts: y inside the slabs
+    assert L.moe_combine_parts(x, 2, rest, rest, 2, 2, 256, x, 0, None, None) == INVALID
+    assert L.moe_combine_parts(x, 0, rest, rest, 2, 2, 256, h, 0, None, None) == INVALID
+    # decode layer: null handle, and the plan query validates without a device
+    assert L.moe_decode_layer(None, x, rest, 1, 2, *(rest,) * 6, None, rest, 1 << 20, None, h,
+                              None) == INVALID
+
+
+def test_ffn_plan_query(L):
+    import paper_2402_07033_amd as m
+    pl = m.moe_expert_ffn_plan(2, 8, 4096, 14336)
+    assert pl["path"] == m.MOE_FFN_STREAM and pl["n_parts"] == 4 and pl["up_tile_rows"] == 0
+    pl = m.moe_expert_ffn_plan(8192, 8, 4096, 14336)
+    assert pl["path"] == m.MOE_FFN_GROUPED and pl["n_parts"] == 1
+    assert pl["up_tile_rows"] >= 128 and pl["down_tile_features"] >= 256
+    assert m.moe_expert_ffn_plan(80, 8, 4096, 14336)["path"] == m.MOE_FFN_MID
+    assert m.moe_expert_ffn_plan(2, 16, 4096, 6400)["n_parts"] == 4
+    with pytest.raises(m.MoeError):
+        m.moe_expert_ffn_plan(16, 8, 4096, 100)
 
 
 def test_workspace_query(L):

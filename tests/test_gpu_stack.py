@@ -187,7 +187,7 @@ def test_stack_seam_on_off_identical(moe):
         W.free()
 
 
-def _run_stack(moe, cfgs, T, k, fused=True):
+def _run_stack(moe, cfgs, T, k, fused=True, free_running=True):
     """cfgs: one MoEConfig per layer.  Returns (gpu final x, oracle result, info)."""
     host_layers, dev_layers = [], []
     for cfg in cfgs:
@@ -205,12 +205,14 @@ def _run_stack(moe, cfgs, T, k, fused=True):
     ref = orc.stack(x0.astype(np.float64), host_layers, k, forced_logits=gpu_logits)
     for l in range(len(cfgs)):
         assert (to_host(idx[l]) == ref["idx"][l]).all(), f"routing differs at layer {l}"
-    free = orc.stack(x0.astype(np.float64), host_layers, k)
-    same = np.mean([np.mean(a == b) for a, b in zip(free["idx"], ref["idx"])])
+    info = {}
+    if free_running:  # information only: the oracle routing on its own logits
+        free = orc.stack(x0.astype(np.float64), host_layers, k)
+        same = np.mean([np.mean(a == b) for a, b in zip(free["idx"], ref["idx"])])
+        info = dict(same_routing_free_running=float(same), err_free=max_rel(to_host(xd), free["x"]))
     for W, _ in dev_layers:
         W.free()
-    return to_host(xd), ref, dict(same_routing_free_running=float(same),
-                                  err_free=max_rel(to_host(xd), free["x"]))
+    return to_host(xd), ref, info
 
 
 @pytest.mark.parametrize("T,L,d,f,fused", [(1, 6, 256, 512, True), (1, 6, 256, 512, False),
@@ -225,10 +227,66 @@ def test_stack_small_shapes(moe, T, L, d, f, fused):
     assert err <= TOL_BF16
 
 
-@pytest.mark.parametrize("T", [1, 16])
-def test_stack_mixtral_shape_two_layers(moe, T):
-    cfgs = [mi.stack_layer_config(l, T) for l in range(2)]
-    x, ref, info = _run_stack(moe, cfgs, T, 2)
+# The stack workload at the Mixtral shape (independent seeded weights per layer, 2.8 GB
+# each): single-token decode through 8 layers (the one-launch seam between blocks, reduction
+# parts added inside it), beam-sized and 512-token prefill through 2 layers (the whole fp64
+# oracle: 2 x 1024 rows).
+@pytest.mark.parametrize("T,L", [(1, 8), (16, 2), (512, 2)])
+def test_stack_mixtral_shape(moe, T, L):
+    cfgs = [mi.stack_layer_config(l, T) for l in range(L)]
+    if T == 512:
+        pl = moe.moe_expert_ffn_plan(T * 2, 8, 4096, 14336)
+        assert (pl["path"], pl["up_tile_rows"]) == (moe.MOE_FFN_GROUPED, 192)
+    x, ref, info = _run_stack(moe, cfgs, T, 2, free_running=(T != 512))
     err = max_rel(x, ref["x"])
-    print(f"stack mixtral T={T} L=2: err={err:.3e} {info}")
+    print(f"stack mixtral T={T} L={L}: err={err:.3e} {info}")
     assert err <= TOL_BF16
+
+
+@pytest.mark.parametrize("T,E,k,k_prev,d,P", [(1, 8, 2, 2, 4096, 4), (4, 8, 2, 2, 512, 2),
+                                              (2, 16, 3, 3, 256, 3)])
+def test_seam_call_with_reduction_parts(moe, T, E, k, k_prev, d, P):
+    """The seam call on P unsummed reduction parts == moe_combine_parts (residual form)
+    followed by moe_norm_route_permute, bit for bit; more than 4 parts are refused."""
+    rng = np.random.default_rng(7 * T + P)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    wg = to_dev((rng.standard_normal((d, E)) / np.sqrt(d)).astype(np.float32))
+    Np, N = T * k_prev, T * k
+    parts = to_dev(rng.standard_normal((P, Np, d)).astype(np.float32))
+    inv = to_dev(rng.permutation(Np).astype(np.int32))
+    wp = to_dev(rng.random((T, k_prev)).astype(np.float32))
+    x0 = (rng.standard_normal((T, d)) * 1.5).astype(np.float32)
+
+    def outs():
+        return (torch.zeros(E, **i32), torch.zeros(E + 1, **i32), torch.zeros(N, **i32),
+                torch.zeros(N, **i32), torch.zeros((N, d), device="cuda"))
+
+    def small():
+        return (torch.zeros((T, d), device="cuda"), torch.zeros((T, E), device="cuda"),
+                torch.zeros((T, k), **i32), torch.zeros((T, k), device="cuda"))
+
+    xa = to_dev(x0.copy())
+    moe.moe_combine_parts(parts, P, inv, wp, y=xa, residual=True)
+    ha, la, ia, wa = small()
+    oa = outs()
+    moe.moe_norm_route_permute(xa, wg, k, 1e-5, ha, la, ia, wa, oa)
+    xin, xout = to_dev(x0.copy()), torch.zeros((T, d), device="cuda")
+    hb, lb, ib, wb = small()
+    ob = outs()
+    moe.moe_combine_norm_route_permute(parts, inv, wp, xin, xout, wg, k, 1e-5, hb, lb, ib, wb, ob,
+                                       n_parts_prev=P)
+    torch.cuda.synchronize()
+    assert torch.equal(xout, xa)
+    assert torch.equal(hb, ha) and torch.equal(lb, la)
+    assert torch.equal(ib, ia) and torch.equal(wb, wa)
+    for a, b in zip(oa, ob):
+        assert torch.equal(a, b)
+    # and against fp64: x_out = x + sum_j w_j * (sum of the parts)
+    yg64 = to_host(parts).astype(np.float64).sum(axis=0)
+    ref = x0.astype(np.float64) + orc.combine(yg64, to_host(inv), to_host(wp).astype(np.float64))
+    assert max_rel(to_host(xout), ref) <= 2e-6
+    five = torch.zeros((5, Np, d), device="cuda")
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_combine_norm_route_permute(five, inv, wp, xin, xout, wg, k, 1e-5, hb, lb, ib, wb,
+                                           ob, n_parts_prev=5)
+    assert ei.value.status == -2
