@@ -139,6 +139,23 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
                         size_t workspace_bytes, float* yg, int path, void* stream);
 
 /*
+ * moe_expert_ffn for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels and results as moe_expert_ffn; the scratch is a static device
+ * array of moe_expert_ffn_noalloc_max_bytes() = 32 MiB inside the library (one copy per GPU,
+ * held until the process ends).  The call allocates nothing and frees nothing.
+ *   Returns MOE_ERR_WORKSPACE when the kernel family that would run needs more scratch
+ *   than that (decode-sized calls fit: the Mixtral shape needs 120 KiB per routed row;
+ *   prefill-sized calls do not -- they take moe_expert_ffn with a caller's workspace).
+ *   All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ *   streams, different host threads) race; serialise them.  Nothing in the array has to
+ *   survive between calls and nothing has to be zero at the start of one.
+ */
+int moe_expert_ffn_noalloc(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                           const int32_t* offsets, int N, float* yg, void* stream);
+size_t moe_expert_ffn_noalloc_max_bytes(void);
+
+/*
  * What moe_expert_ffn_path would run for these sizes (HOST query; nothing is launched).
  *   path     the kernel family (AUTO resolved; MOE_FFN_AUTO for fp32 weights, which have
  *            one kernel pair of their own)

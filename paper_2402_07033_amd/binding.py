@@ -20,7 +20,8 @@ _lib = None
 EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_expert_ffn_plan",
-           "moe_expert_ffn_parts", "moe_combine", "moe_combine_parts", "moe_decode_layer",
+           "moe_expert_ffn_parts", "moe_expert_ffn_noalloc", "moe_expert_ffn_noalloc_max_bytes",
+           "moe_combine", "moe_combine_parts", "moe_decode_layer",
            "moe_rmsnorm", "moe_router_logits", "moe_residual_add", "moe_route_permute",
            "moe_norm_route_permute", "moe_combine_residual", "moe_combine_norm_route_permute",
            "moe_rmsnorm_router_logits")
@@ -87,6 +88,10 @@ def lib():
         L.moe_combine_norm_route_permute.argtypes = ([vp, i32, vp, vp, i32, vp, vp, vp] + [i32] * 4 +
                                                      [f32] + [vp] * 10)
         L.moe_combine_norm_route_permute.restype = C.c_int
+        L.moe_expert_ffn_noalloc.argtypes = [vp, vp, i32, vp, i32, vp, vp]
+        L.moe_expert_ffn_noalloc.restype = C.c_int
+        L.moe_expert_ffn_noalloc_max_bytes.argtypes = []
+        L.moe_expert_ffn_noalloc_max_bytes.restype = C.c_size_t
         L.moe_expert_ffn_plan.argtypes = [i32] * 6 + [C.POINTER(FfnPlan)]
         L.moe_expert_ffn_plan.restype = C.c_int
         L.moe_expert_ffn_parts.argtypes = [vp, vp, i32, vp, i32, vp, C.c_size_t, vp, i32,
@@ -266,6 +271,24 @@ def moe_expert_ffn_parts(W: "PackedWeights", xg: torch.Tensor, offsets: torch.Te
                                       yg_parts.shape[0], C.byref(n), _stream(stream)),
            "moe_expert_ffn_parts")
     return int(n.value)
+
+
+def moe_expert_ffn_noalloc(W: "PackedWeights", xg: torch.Tensor, offsets: torch.Tensor,
+                           yg: torch.Tensor, stream=None):
+    """moe_expert_ffn on the library's static scratch: allocates nothing, so yg is the
+    caller's (fp32 [N,d])."""
+    _dev(offsets, torch.int32, "offsets")
+    _dev(yg, torch.float32, "yg")
+    if not xg.is_cuda or not xg.is_contiguous():
+        raise TypeError("xg: expected a contiguous device tensor")
+    _check(lib().moe_expert_ffn_noalloc(C.c_void_p(W.handle), _ptr(xg), _act_dtype(xg),
+                                        _ptr(offsets), xg.shape[0], _ptr(yg), _stream(stream)),
+           "moe_expert_ffn_noalloc")
+    return yg
+
+
+def moe_expert_ffn_noalloc_max_bytes() -> int:
+    return int(lib().moe_expert_ffn_noalloc_max_bytes())
 
 
 def moe_combine_parts(yg_parts: torch.Tensor, n_parts: int, inv_perm: torch.Tensor,

@@ -29,7 +29,7 @@ static inline bool ranges_overlap(const void* a, size_t an, const void* b, size_
 //   (many experts with a handful of rows each: 11 % ahead at 6 rows per expert, 5 % behind
 //   at 12; with 8 experts the window is 73..80 rows, so this is a path of E >= 16 layers);
 //   above that the LDS-tiled grouped GEMM, whose smaller tiles stream the weights too.
-static int auto_path(int N, int E, int d, int f) {
+int moe_ffn_auto_path(int N, int E, int d, int f) {
     if (N <= 72 && moe_ffn_stream_supported(d, f)) return MOE_FFN_STREAM;
     if ((long long)N <= (long long)MOE_MID_MAX_ROWS * E && moe_ffn_mid_supported(N, E, d, f))
         return MOE_FFN_MID;
@@ -125,7 +125,7 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
         if (act_dtype != MOE_F32 || path != MOE_FFN_AUTO) return MOE_ERR_UNSUPPORTED;
         return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
     }
-    if (path == MOE_FFN_AUTO) path = auto_path(N, W->E, W->d, W->f);
+    if (path == MOE_FFN_AUTO) path = moe_ffn_auto_path(N, W->E, W->d, W->f);
     if (path == MOE_FFN_STREAM)
         return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg, nullptr, s);
     if (path == MOE_FFN_MID)
@@ -155,7 +155,7 @@ int moe_expert_ffn_plan(int N, int E, int d, int f, moe_dtype_t w_dtype, int pat
         plan->path = MOE_FFN_AUTO;  // the all-fp32 kernels are no family of their own
         return MOE_OK;
     }
-    if (path == MOE_FFN_AUTO) path = auto_path(N, E, d, f);
+    if (path == MOE_FFN_AUTO) path = moe_ffn_auto_path(N, E, d, f);
     plan->path = path;
     if (path == MOE_FFN_STREAM) {
         if (!moe_ffn_stream_supported(d, f)) return MOE_ERR_UNSUPPORTED;
@@ -174,7 +174,7 @@ int moe_expert_ffn_parts(const moe_weights_t* W, const void* xg, moe_dtype_t act
     if (!W || !n_parts || max_parts < 1) return MOE_ERR_INVALID_ARG;
     *n_parts = 1;
     if (N < 0 || N >= MOE_MAX_N) return MOE_ERR_INVALID_ARG;
-    const bool stream_path = W->dtype == MOE_BF16 && auto_path(N, W->E, W->d, W->f) == MOE_FFN_STREAM;
+    const bool stream_path = W->dtype == MOE_BF16 && moe_ffn_auto_path(N, W->E, W->d, W->f) == MOE_FFN_STREAM;
     if (!stream_path || N == 0)
         return moe_expert_ffn_path(W, xg, act_dtype, offsets, N, workspace, workspace_bytes,
                                    yg_parts, MOE_FFN_AUTO, stream);

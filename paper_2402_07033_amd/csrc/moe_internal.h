@@ -60,6 +60,9 @@ int moe_current_device();
 // Number of compute units of the current device (cached per device; 256 on MI355X).
 int moe_num_cus();
 
+// AUTO's choice among MOE_FFN_STREAM / MID / GROUPED for bf16 weights (moe_api.hip).
+int moe_ffn_auto_path(int N, int E, int d, int f);
+
 // ---- expert FFN kernel families (each returns a moe_status_t) ----------------
 size_t moe_ffn_f32_workspace(int N, int E, int d, int f);
 int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* offsets, int N,
