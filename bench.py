@@ -172,7 +172,8 @@ def make_inputs(torch, moe, wl, n_inputs, seed):
 class Step:
     """Preallocated buffers + the C-ABI calls of one step."""
 
-    def __init__(self, torch, moe, T, x_dtype, one_call=True, fused_gate=False):
+    def __init__(self, torch, moe, T, x_dtype, one_call=True, fused_gate=False,
+                 gathered_copy=False):
         N = T * K
         self.one_call = (one_call and T <= 16 and N <= 64 and E <= 16 and x_dtype == torch.float32)
         self.fused_gate = fused_gate and not self.one_call and T <= 16 and x_dtype == torch.float32
@@ -182,8 +183,11 @@ class Step:
         self.moe = moe
         self.idx = torch.empty((T, K), **i32)
         self.w = torch.empty((T, K), **f32)
-        # the one-call step reads the token rows directly: no gathered copy is asked for
-        xg = None if self.one_call else torch.empty((N, D), dtype=x_dtype, device="cuda")
+        # the one-call step and moe_expert_ffn_tokens read the token rows directly: no
+        # gathered copy is asked for
+        self.tokens_entry = not self.one_call and not self.fused_gate and not gathered_copy
+        xg = (None if self.one_call or self.tokens_entry
+              else torch.empty((N, D), dtype=x_dtype, device="cuda"))
         self.perm_out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
                          torch.empty(N, **i32), xg)
         adt = moe.MOE_BF16 if x_dtype == torch.bfloat16 else moe.MOE_F32
@@ -198,6 +202,8 @@ class Step:
             return "moe_decode_layer"
         if self.fused_gate:
             return "moe_route_permute, moe_expert_ffn, moe_combine"
+        if self.tokens_entry:
+            return "moe_route, moe_permute (indices only), moe_expert_ffn_tokens, moe_combine"
         return "moe_route, moe_permute, moe_expert_ffn, moe_combine"
 
     def run(self, W, x, logits, ev=None, events=None, stream=0):
@@ -215,11 +221,14 @@ class Step:
             counts, offsets, perm, inv_perm, xg = self.perm_out
         else:
             moe.moe_route(logits, K, self.idx, self.w)
-            counts, offsets, perm, inv_perm, xg = moe.moe_permute(self.idx, E, x,
-                                                                  out=self.perm_out)
+            counts, offsets, perm, inv_perm, xg = moe.moe_permute(
+                self.idx, E, None if self.tokens_entry else x, out=self.perm_out)
         if ev is not None:
             events.record(ev[0], stream)
-        moe.moe_expert_ffn(W, xg, offsets, workspace=self.ws, yg=self.yg, path=self.ffn_path)
+        if self.tokens_entry:
+            moe.moe_expert_ffn_tokens(W, x, K, perm, offsets, workspace=self.ws, yg=self.yg)
+        else:
+            moe.moe_expert_ffn(W, xg, offsets, workspace=self.ws, yg=self.yg, path=self.ffn_path)
         if ev is not None:
             events.record(ev[2], stream)
         moe.moe_combine(self.yg, inv_perm, self.w, self.y)
@@ -284,7 +293,8 @@ def run_layer_workload(torch, moe, name, wl, sets, args, steps, warmup, host_w=N
     xs, lgs = make_inputs(torch, moe, wl, n_inputs, 4242)
     step = Step(torch, moe, T, xs[0].dtype,
                 one_call=not args.four_calls and args.ffn_path == "auto",
-                fused_gate=args.fused_gate)
+                fused_gate=args.fused_gate,
+                gathered_copy=args.gathered_copy or args.ffn_path != "auto")
     step.ffn_path = {"auto": moe.MOE_FFN_AUTO, "stream": moe.MOE_FFN_STREAM,
                      "grouped": moe.MOE_FFN_GROUPED, "mid": moe.MOE_FFN_MID}[args.ffn_path]
     stream = torch.cuda.current_stream().cuda_stream
@@ -567,6 +577,10 @@ def main():
     ap.add_argument("--four-calls", action="store_true",
                     help="decode-sized workloads: time moe_route, moe_permute, moe_expert_ffn, "
                          "moe_combine instead of the one-call moe_decode_layer")
+    ap.add_argument("--gathered-copy", action="store_true",
+                    help="four-call steps: let moe_permute write the gathered rows xg and run "
+                         "moe_expert_ffn on them (default: moe_expert_ffn_tokens reads the token "
+                         "rows through perm)")
     ap.add_argument("--fused-gate", action="store_true",
                     help="with --four-calls: use the one-launch moe_route_permute instead of "
                          "moe_route + moe_permute (same outputs)")

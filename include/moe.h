@@ -139,6 +139,19 @@ int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_
                         size_t workspace_bytes, float* yg, int path, void* stream);
 
 /*
+ * moe_expert_ffn without the gathered copy (Sec. 3.3: the experts consume the tokens the
+ * gate sent them; where those rows live is an implementation matter): the kernels read the
+ * batched row i as x[perm[i] / k, :], so moe_permute can be called without x / xg and the
+ * N x d copy is never written or read back.  Same results as moe_expert_ffn on the xg that
+ * moe_permute would have produced, bit for bit.
+ *   x [T,d] of act_dtype; perm [T*k] int32 as written by moe_permute; offsets as above;
+ *   workspace >= moe_expert_ffn_workspace(T*k, ...); yg [T*k,d] fp32 out
+ */
+int moe_expert_ffn_tokens(const moe_weights_t* W, const void* x, moe_dtype_t act_dtype, int T,
+                          int k, const int32_t* perm, const int32_t* offsets, void* workspace,
+                          size_t workspace_bytes, float* yg, void* stream);
+
+/*
  * moe_expert_ffn for callers that cannot allocate device memory and have no workspace to
  * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, kernels and results as moe_expert_ffn; the scratch is a static device

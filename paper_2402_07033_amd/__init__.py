@@ -10,7 +10,7 @@ from .binding import (MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_
                       moe_combine, moe_combine_norm_route_permute, moe_combine_parts,
                       moe_combine_residual, moe_decode_layer, moe_expert_ffn,
                       moe_expert_ffn_noalloc, moe_expert_ffn_noalloc_max_bytes,
-                      moe_expert_ffn_parts, moe_expert_ffn_plan, moe_expert_ffn_workspace,
+                      moe_expert_ffn_parts, moe_expert_ffn_plan, moe_expert_ffn_tokens, moe_expert_ffn_workspace,
                       moe_hbm_read_probe, moe_layer, moe_mfma_rate_probe,
                       moe_norm_route_permute, moe_permute, moe_residual_add, moe_rmsnorm,
                       moe_rmsnorm_router_logits, moe_route, moe_route_permute,
@@ -22,7 +22,7 @@ __all__ = [
     "MoeError", "PackedWeights", "StackBuffers", "lib", "lib_path", "moe_combine",
     "moe_combine_norm_route_permute", "moe_combine_parts", "moe_combine_residual",
     "moe_decode_layer", "moe_expert_ffn", "moe_expert_ffn_noalloc",
-    "moe_expert_ffn_noalloc_max_bytes", "moe_expert_ffn_parts", "moe_expert_ffn_plan",
+    "moe_expert_ffn_noalloc_max_bytes", "moe_expert_ffn_parts", "moe_expert_ffn_tokens", "moe_expert_ffn_plan",
     "moe_expert_ffn_workspace", "moe_hbm_read_probe", "moe_layer", "moe_mfma_rate_probe",
     "moe_norm_route_permute", "moe_permute", "moe_residual_add", "moe_rmsnorm",
     "moe_rmsnorm_router_logits", "moe_route", "moe_route_permute", "moe_router_logits",

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_expert_ffn_plan",
-           "moe_expert_ffn_parts", "moe_expert_ffn_noalloc", "moe_expert_ffn_noalloc_max_bytes",
+           "moe_expert_ffn_parts", "moe_expert_ffn_tokens", "moe_expert_ffn_noalloc", "moe_expert_ffn_noalloc_max_bytes",
            "moe_combine", "moe_combine_parts", "moe_decode_layer",
            "moe_rmsnorm", "moe_router_logits", "moe_residual_add", "moe_route_permute",
            "moe_norm_route_permute", "moe_combine_residual", "moe_combine_norm_route_permute",
@@ -88,6 +88,8 @@ def lib():
         L.moe_combine_norm_route_permute.argtypes = ([vp, i32, vp, vp, i32, vp, vp, vp] + [i32] * 4 +
                                                      [f32] + [vp] * 10)
         L.moe_combine_norm_route_permute.restype = C.c_int
+        L.moe_expert_ffn_tokens.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, C.c_size_t, vp, vp]
+        L.moe_expert_ffn_tokens.restype = C.c_int
         L.moe_expert_ffn_noalloc.argtypes = [vp, vp, i32, vp, i32, vp, vp]
         L.moe_expert_ffn_noalloc.restype = C.c_int
         L.moe_expert_ffn_noalloc_max_bytes.argtypes = []
@@ -271,6 +273,27 @@ def moe_expert_ffn_parts(W: "PackedWeights", xg: torch.Tensor, offsets: torch.Te
                                       yg_parts.shape[0], C.byref(n), _stream(stream)),
            "moe_expert_ffn_parts")
     return int(n.value)
+
+
+def moe_expert_ffn_tokens(W: "PackedWeights", x: torch.Tensor, k: int, perm: torch.Tensor,
+                          offsets: torch.Tensor, workspace=None, yg=None, stream=None):
+    """moe_expert_ffn reading row i as x[perm[i] / k]: no gathered copy.  x [T,d]."""
+    _dev(perm, torch.int32, "perm")
+    _dev(offsets, torch.int32, "offsets")
+    if not x.is_cuda or not x.is_contiguous():
+        raise TypeError("x: expected a contiguous device tensor")
+    T = x.shape[0]
+    N = T * k
+    adt = _act_dtype(x)
+    if workspace is None:
+        need = moe_expert_ffn_workspace(N, W.E, W.d, W.f, adt)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if yg is None:
+        yg = torch.empty((N, W.d), dtype=torch.float32, device=x.device)
+    _check(lib().moe_expert_ffn_tokens(C.c_void_p(W.handle), _ptr(x), adt, T, k, _ptr(perm),
+                                       _ptr(offsets), _ptr(workspace), workspace.numel(),
+                                       _ptr(yg), _stream(stream)), "moe_expert_ffn_tokens")
+    return yg
 
 
 def moe_expert_ffn_noalloc(W: "PackedWeights", xg: torch.Tensor, offsets: torch.Tensor,
@@ -510,7 +533,10 @@ class StackBuffers:
         self.ws = torch.empty(max(moe_expert_ffn_workspace(N, E, d, f, MOE_F32), 256),
                               dtype=torch.uint8, device=device)
         # the second projection's reduction parts (decode kernels; slab 0 is yg otherwise)
-        self.max_parts = max(1, moe_expert_ffn_plan(N, E, d, f, MOE_BF16)["n_parts"])
+        plan = moe_expert_ffn_plan(N, E, d, f, MOE_BF16)
+        self.max_parts = max(1, plan["n_parts"])
+        # prefill-sized passes read the normalised rows through perm: no gathered copy
+        self.rows_through_perm = plan["path"] != MOE_FFN_STREAM
         self.yg_parts = torch.empty((self.max_parts, N, d), **f32)
         self.yg = self.yg_parts[0]
         self.y = torch.empty((T, d), **f32)
@@ -561,15 +587,24 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
                 moe_rmsnorm(cur, eps, bufs.h, stream=stream)
                 moe_router_logits(bufs.h, w_gate, bufs.logits, stream=stream)
             moe_route(bufs.logits, k, rs["idx"], rs["w"], stream=stream)
-            _, offsets, _, inv_perm, xg = moe_permute(rs["idx"], W.E, bufs.h, out=rs["perm_out"],
-                                                      stream=stream)
+            if fused and bufs.rows_through_perm and W.dtype == MOE_BF16:
+                po = rs["perm_out"][:4] + (None,)
+                _, offsets, perm, inv_perm, xg = moe_permute(rs["idx"], W.E, None, out=po,
+                                                             stream=stream)
+            else:
+                _, offsets, perm, inv_perm, xg = moe_permute(rs["idx"], W.E, bufs.h,
+                                                             out=rs["perm_out"], stream=stream)
         if logits_out is not None:
             logits_out.append(bufs.logits.clone())
         if idx_out is not None:
             idx_out.append(rs["idx"].clone())
         if on_layer is not None:
             on_layer(li)
-        if use_parts:
+        if xg is None:
+            n_parts = 1
+            moe_expert_ffn_tokens(W, bufs.h, k, perm, offsets, workspace=bufs.ws, yg=bufs.yg,
+                                  stream=stream)
+        elif use_parts:
             n_parts = moe_expert_ffn_parts(W, xg, offsets, bufs.yg_parts, workspace=bufs.ws,
                                            stream=stream)
         else:

@@ -36,6 +36,36 @@ int moe_ffn_auto_path(int N, int E, int d, int f) {
     return MOE_FFN_GROUPED;
 }
 
+// moe_expert_ffn and its variants: validation, then the kernel family.  With `perm` the
+// batched row i is read as xg[perm[i] / k] (xg is then the token array).
+static int ffn_dispatch(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
+                        const int32_t* perm, int k, const int32_t* offsets, int N, void* workspace,
+                        size_t workspace_bytes, float* yg, int path, void* stream) {
+    if (!W || N < 0 || N >= MOE_MAX_N) return MOE_ERR_INVALID_ARG;
+    if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (path != MOE_FFN_AUTO && path != MOE_FFN_STREAM && path != MOE_FFN_GROUPED &&
+        path != MOE_FFN_MID)
+        return MOE_ERR_INVALID_ARG;
+    if (!offsets) return MOE_ERR_INVALID_ARG;
+    if (N == 0) return MOE_OK;
+    if (!xg || !yg || !moe_aligned16(xg) || !moe_aligned16(yg)) return MOE_ERR_INVALID_ARG;
+    if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
+    if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, act_dtype))
+        return MOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (W->dtype == MOE_F32) {
+        if (act_dtype != MOE_F32 || path != MOE_FFN_AUTO) return MOE_ERR_UNSUPPORTED;
+        return moe_ffn_f32_launch(W, (const float*)xg, perm, k, offsets, N, workspace, yg, s);
+    }
+    if (path == MOE_FFN_AUTO) path = moe_ffn_auto_path(N, W->E, W->d, W->f);
+    if (path == MOE_FFN_STREAM)
+        return moe_ffn_stream_launch(W, xg, act_dtype, perm, k, offsets, N, workspace, yg, nullptr, s);
+    if (path == MOE_FFN_MID)
+        return moe_ffn_mid_launch(W, xg, act_dtype, perm, k, offsets, N, workspace, yg, s);
+    return moe_ffn_grouped_launch(W, xg, act_dtype, perm, k, offsets, N, workspace, yg, s);
+}
+
 extern "C" {
 
 const char* moe_status_string(int status) {
@@ -108,29 +138,17 @@ size_t moe_expert_ffn_workspace(int N, int E, int d, int f, moe_dtype_t act_dtyp
 int moe_expert_ffn_path(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
                         const int32_t* offsets, int N, void* workspace, size_t workspace_bytes,
                         float* yg, int path, void* stream) {
-    if (!W || N < 0 || N >= MOE_MAX_N) return MOE_ERR_INVALID_ARG;
-    if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
-    if (path != MOE_FFN_AUTO && path != MOE_FFN_STREAM && path != MOE_FFN_GROUPED &&
-        path != MOE_FFN_MID)
-        return MOE_ERR_INVALID_ARG;
-    if (!offsets) return MOE_ERR_INVALID_ARG;
-    if (N == 0) return MOE_OK;
-    if (!xg || !yg || !moe_aligned16(xg) || !moe_aligned16(yg)) return MOE_ERR_INVALID_ARG;
-    if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
-    if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, act_dtype))
-        return MOE_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+    return ffn_dispatch(W, xg, act_dtype, nullptr, 1, offsets, N, workspace, workspace_bytes, yg,
+                        path, stream);
+}
 
-    if (W->dtype == MOE_F32) {
-        if (act_dtype != MOE_F32 || path != MOE_FFN_AUTO) return MOE_ERR_UNSUPPORTED;
-        return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, workspace, yg, s);
-    }
-    if (path == MOE_FFN_AUTO) path = moe_ffn_auto_path(N, W->E, W->d, W->f);
-    if (path == MOE_FFN_STREAM)
-        return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg, nullptr, s);
-    if (path == MOE_FFN_MID)
-        return moe_ffn_mid_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
-    return moe_ffn_grouped_launch(W, xg, act_dtype, offsets, N, workspace, yg, s);
+int moe_expert_ffn_tokens(const moe_weights_t* W, const void* x, moe_dtype_t act_dtype, int T,
+                          int k, const int32_t* perm, const int32_t* offsets, void* workspace,
+                          size_t workspace_bytes, float* yg, void* stream) {
+    if (!W || !tek_ok(T, W->E, k)) return MOE_ERR_INVALID_ARG;
+    if (T > 0 && (!perm || !moe_aligned16(perm))) return MOE_ERR_INVALID_ARG;
+    return ffn_dispatch(W, x, act_dtype, perm, k, offsets, T * k, workspace, workspace_bytes, yg,
+                        MOE_FFN_AUTO, stream);
 }
 
 int moe_expert_ffn(const moe_weights_t* W, const void* xg, moe_dtype_t act_dtype,
@@ -185,7 +203,7 @@ int moe_expert_ffn_parts(const moe_weights_t* W, const void* xg, moe_dtype_t act
     if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
     if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, act_dtype))
         return MOE_ERR_WORKSPACE;
-    return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, workspace, yg_parts, n_parts,
+    return moe_ffn_stream_launch(W, xg, act_dtype, nullptr, 1, offsets, N, workspace, yg_parts, n_parts,
                                  (hipStream_t)stream);
 }
 

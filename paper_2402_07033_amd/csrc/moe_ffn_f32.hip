@@ -31,6 +31,7 @@ __device__ __forceinline__ bool f32_find_tile(const int32_t* __restrict__ offset
 // !UP:  out[i,c] = sum_r act[i,r] wA[e,r,c]
 template <bool UP>
 __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ act,
+                                                      const int32_t* __restrict__ perm, int perm_k,
                                                       const float* __restrict__ wA,
                                                       const float* __restrict__ wB,
                                                       const int32_t* __restrict__ offsets, int E,
@@ -52,7 +53,13 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
         // activations: 32 rows x 16 k (2 per thread), zero beyond the segment
         for (int i = tid; i < F32_BM * F32_BK; i += 256) {
             const int r = i / F32_BK, kk = i % F32_BK;
-            sX[kk][r] = (r < rows) ? act[(size_t)(row0 + r) * K + k0 + kk] : 0.f;
+            // with perm the batched row i is act[perm[i] / perm_k] (the token array itself)
+            float v = 0.f;
+            if (r < rows) {
+                const int src = perm ? perm[row0 + r] / perm_k : row0 + r;
+                v = act[(size_t)src * K + k0 + kk];
+            }
+            sX[kk][r] = v;
         }
         // weights: 16 k x 64 features (4 per thread)
         for (int i = tid; i < F32_BK * F32_BN; i += 256) {
@@ -97,18 +104,18 @@ size_t moe_ffn_f32_workspace(int N, int E, int d, int f) {
     return (size_t)N * f * sizeof(float);
 }
 
-int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* offsets, int N,
-                       void* ws, float* yg, hipStream_t s) {
+int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* perm, int k,
+                       const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
     const int max_tiles = N / F32_BM + W->E;  // >= sum_e ceil(M_e / BM)
     if (max_tiles > 65535) return MOE_ERR_UNSUPPORTED;  // gridDim.y limit
     float* h = (float*)ws;
     const unsigned ty = (unsigned)max_tiles;
     hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3((unsigned)(W->f / F32_BN), ty), dim3(256), 0, s,
-                       xg, (const float*)W->w1f, (const float*)W->w3f, offsets, W->E, N, W->d, W->f,
-                       h);
+                       xg, perm, k, (const float*)W->w1f, (const float*)W->w3f, offsets, W->E, N, W->d,
+                       W->f, h);
     moe_record_mid_event(s);
     hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3((unsigned)(W->d / F32_BN), ty), dim3(256), 0, s,
-                       (const float*)h, (const float*)W->w2f, (const float*)nullptr, offsets, W->E,
-                       N, W->f, W->d, yg);
+                       (const float*)h, (const int32_t*)nullptr, 1, (const float*)W->w2f,
+                       (const float*)nullptr, offsets, W->E, N, W->f, W->d, yg);
     return moe_launch_status();
 }

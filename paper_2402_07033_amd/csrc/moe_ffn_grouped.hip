@@ -749,7 +749,8 @@ int moe_ffn_grouped_plan(int N, int E, int d, int f, moe_ffn_plan_t* plan) {
 }
 
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                           const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
+                           const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
+                           float* yg, hipStream_t s) {
     const int d = W->d, f = W->f, E = W->E;
     GgVariant vu, vd;
     if (!gg_choose(N, E, d, f, vu, vd)) return MOE_ERR_UNSUPPORTED;
@@ -775,11 +776,11 @@ int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act
     }
 
     if (act_dtype == MOE_BF16)
-        hipLaunchKernelGGL(gg_pack_kernel<true>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets, E,
-                           N, d, xp);
+        hipLaunchKernelGGL(gg_pack_kernel<true>, dim3((unsigned)nb), dim3(256), 0, s, xg, perm, k,
+                           offsets, E, N, d, xp);
     else
-        hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets,
-                           E, N, d, xp);
+        hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, perm, k,
+                           offsets, E, N, d, xp);
 
     // scratch of the pieces of left-over tiles, behind the two fragment buffers
     float* part = (float*)((unsigned char*)ws + gg_align256(nb * 16 * d * 2) +

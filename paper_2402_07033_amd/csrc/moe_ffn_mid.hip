@@ -423,7 +423,8 @@ size_t moe_ffn_mid_workspace(int N, int E, int d, int f) {
 }
 
 int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                       const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s) {
+                       const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
+                       float* yg, hipStream_t s) {
     const int d = W->d, f = W->f, E = W->E;
     if (!moe_ffn_mid_supported(N, E, d, f)) return MOE_ERR_UNSUPPORTED;
     const size_t nb = md_max_blocks(N, E);
@@ -445,11 +446,11 @@ int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dty
     }
 
     if (act_dtype == MOE_BF16)
-        hipLaunchKernelGGL(gg_pack_kernel<true>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets, E,
-                           N, d, xp);
+        hipLaunchKernelGGL(gg_pack_kernel<true>, dim3((unsigned)nb), dim3(256), 0, s, xg, perm, k,
+                           offsets, E, N, d, xp);
     else
-        hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, offsets,
-                           E, N, d, xp);
+        hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, perm, k,
+                           offsets, E, N, d, xp);
 
     float* part = (float*)((unsigned char*)ws + md_align256(nb * 16 * d * 2) + md_align256(nb * 16 * f * 2));
     const unsigned max_units_per_nt = (unsigned)md_max_tiles(N, E);

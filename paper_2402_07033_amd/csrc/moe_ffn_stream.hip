@@ -40,6 +40,8 @@
 struct StreamArgs {
     const u32x4_t* wfrag;  // fragment-ordered weights
     const void* act;       // [N,K] fp32 or bf16
+    const int32_t* row_perm;  // or null; else row i of the activations is act[row_perm[i] / row_k]
+    int row_k;
     const int32_t* offsets;
     float* out;       // up: h [N,C]; down: yg [N,C] (P == 1) or the slabs [P][N][C]
     size_t part_stride;  // floats between two slabs of `out` (0 when P == 1)
@@ -65,10 +67,12 @@ struct StreamArgs {
 template <int KSW, bool ACT_BF16>
 __device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 1 : 2],
                                                 const void* actp, int K, int row0, int rows,
-                                                int ks0, int lane, const int* rowmap) {
+                                                int ks0, int lane, const int* rowmap,
+                                                const int32_t* perm, int perm_k) {
     const int t = lane & 15, kq = lane >> 4;
     int src_row = row0 + t;
     if (rowmap && t < rows) src_row = rowmap[row0 + t];
+    if (perm && t < rows) src_row = perm[row0 + t] / perm_k;
 #pragma unroll
     for (int s = 0; s < KSW; s++) {
         const size_t off = (size_t)src_row * K + (size_t)(ks0 + s) * 32 + kq * 8;
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
         const int row0 = s_tr0[tile], rows = s_trn[tile];
         if (tile != cur_tile || part != cur_part) {
             stream_load_act<KSW, ACT_BF16>(act, a.act, a.K, row0, rows, part * part_ks + wave_ks,
-                                           lane, rowmap);
+                                           lane, rowmap, a.row_perm, a.row_k);
             cur_tile = tile;
             cur_part = part;
         }
@@ -442,15 +446,17 @@ int moe_ffn_stream_parts(int d, int f) {
 // are added by a third launch.  Else `out` holds moe_ffn_stream_parts(d, f) slabs [N,d] that
 // are left for the caller to add, and *n_parts receives their number.
 int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                          const int32_t* offsets, int N, void* ws, float* out, int* n_parts,
-                          hipStream_t s) {
+                          const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
+                          float* out, int* n_parts, hipStream_t s) {
     const int d = W->d, f = W->f, E = W->E;
     StreamPlan pl;
     if (!stream_plan(d, f, pl) || !stream_shape_ok(pl, N, E, d, f)) return MOE_ERR_UNSUPPORTED;
     float* h = (float*)ws;
     float* slabs = n_parts ? out
                            : (float*)((unsigned char*)ws + st_align256((size_t)N * f * sizeof(float)));
-    const StreamArgs up = stream_args_up(W, pl, xg, offsets, N, h);
+    StreamArgs up = stream_args_up(W, pl, xg, offsets, N, h);
+    up.row_perm = perm;
+    up.row_k = k;
     int rc = (act_dtype == MOE_BF16) ? stream_dispatch<2, true, false>(pl.KSWu, pl.Wu, s, up)
                                      : stream_dispatch<2, false, false>(pl.KSWu, pl.Wu, s, up);
     if (rc != MOE_OK) return rc;

@@ -37,9 +37,12 @@ __device__ __forceinline__ bool gg_find_block(const int32_t* __restrict__ offset
 
 // ------------------------------------------------------------------- pack ----
 // One workgroup per packed block: rows [row0 + 16*b, +16) of a segment become
-// d/32 B-operand fragments; rows past the segment end are zero.
+// d/32 B-operand fragments; rows past the segment end are zero.  With `perm` the batched
+// row i is read as xg[perm[i] / k]: xg is then the token array itself and the gathered copy
+// is never materialised.
 template <bool ACT_BF16>
 __global__ __launch_bounds__(256) void gg_pack_kernel(const void* __restrict__ xg,
+                                                      const int32_t* __restrict__ perm, int k,
                                                       const int32_t* __restrict__ offsets, int E,
                                                       int N, int d, u32x4_t* __restrict__ xp) {
     SegInfo si;
@@ -52,7 +55,8 @@ __global__ __launch_bounds__(256) void gg_pack_kernel(const void* __restrict__ x
         const int r = b * 16 + t;
         u32x4_t v = {0u, 0u, 0u, 0u};
         if (r < si.rows) {
-            const size_t off = (size_t)(si.row0 + r) * d + (size_t)ks * 32 + kq * 8;
+            const int src = perm ? perm[si.row0 + r] / k : si.row0 + r;
+            const size_t off = (size_t)src * d + (size_t)ks * 32 + kq * 8;
             if (ACT_BF16) {
                 v = *(const u32x4_t*)((const uint16_t*)xg + off);
             } else {

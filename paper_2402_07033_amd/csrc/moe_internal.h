@@ -65,15 +65,17 @@ int moe_ffn_auto_path(int N, int E, int d, int f);
 
 // ---- expert FFN kernel families (each returns a moe_status_t) ----------------
 size_t moe_ffn_f32_workspace(int N, int E, int d, int f);
-int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* offsets, int N,
-                       void* ws, float* yg, hipStream_t s);
+// All launchers: with `perm` (device, or null) the batched row i of the activations is read
+// as xg[perm[i] / k], i.e. xg is the token array and no gathered copy exists.
+int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* perm, int k,
+                       const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
 
 bool moe_ffn_stream_supported(int d, int f);
 size_t moe_ffn_stream_workspace(int N, int E, int d, int f);
 int moe_ffn_stream_parts(int d, int f);  // reduction parts of the second projection (0: unsupported)
 int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                          const int32_t* offsets, int N, void* ws, float* out, int* n_parts,
-                          hipStream_t s);
+                          const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
+                          float* out, int* n_parts, hipStream_t s);
 bool moe_ffn_stream_decode_supported(int T, int E, int k, int d, int f);
 int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const float* logits, int T,
                                  int k, int32_t* idx, float* weights, int32_t* counts,
@@ -84,12 +86,14 @@ int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const flo
 size_t moe_ffn_grouped_workspace(int N, int E, int d, int f);
 int moe_ffn_grouped_plan(int N, int E, int d, int f, moe_ffn_plan_t* plan);  // fills the tile fields
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                           const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
+                           const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
+                           float* yg, hipStream_t s);
 
 bool moe_ffn_mid_supported(int N, int E, int d, int f);
 size_t moe_ffn_mid_workspace(int N, int E, int d, int f);
 int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
-                       const int32_t* offsets, int N, void* ws, float* yg, hipStream_t s);
+                       const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
+                       float* yg, hipStream_t s);
 
 // ---- small device helpers ------------------------------------------------------
 #ifdef __HIPCC__

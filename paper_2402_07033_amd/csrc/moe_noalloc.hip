@@ -53,11 +53,11 @@ int moe_expert_ffn_noalloc(const moe_weights_t* W, const void* xg, moe_dtype_t a
     void* ptr = noalloc_scratch_ptr();
     if (!ptr) return MOE_ERR_HIP;
     hipStream_t s = (hipStream_t)stream;
-    if (W->dtype == MOE_F32) return moe_ffn_f32_launch(W, (const float*)xg, offsets, N, ptr, yg, s);
+    if (W->dtype == MOE_F32) return moe_ffn_f32_launch(W, (const float*)xg, nullptr, 1, offsets, N, ptr, yg, s);
     if (path == MOE_FFN_STREAM)
-        return moe_ffn_stream_launch(W, xg, act_dtype, offsets, N, ptr, yg, nullptr, s);
-    if (path == MOE_FFN_MID) return moe_ffn_mid_launch(W, xg, act_dtype, offsets, N, ptr, yg, s);
-    return moe_ffn_grouped_launch(W, xg, act_dtype, offsets, N, ptr, yg, s);
+        return moe_ffn_stream_launch(W, xg, act_dtype, nullptr, 1, offsets, N, ptr, yg, nullptr, s);
+    if (path == MOE_FFN_MID) return moe_ffn_mid_launch(W, xg, act_dtype, nullptr, 1, offsets, N, ptr, yg, s);
+    return moe_ffn_grouped_launch(W, xg, act_dtype, nullptr, 1, offsets, N, ptr, yg, s);
 }
 
 }  // extern "C"

@@ -204,6 +204,37 @@ def test_mid_path_is_deterministic(moe):
     W.free()
 
 
+@pytest.mark.parametrize("T,d,f,E,k,wdt,xdt,path_name", [
+    (16, 256, 512, 8, 2, mi.F32, mi.F32, "fp32"), (70, 128, 192, 3, 1, mi.F32, mi.F32, "fp32"),
+    (16, 512, 1024, 8, 2, mi.BF16, mi.F32, "stream"), (9, 256, 1600, 16, 2, mi.BF16, mi.BF16, "stream"),
+    (60, 512, 1024, 16, 2, mi.BF16, mi.BF16, "mid"), (300, 512, 1024, 8, 2, mi.BF16, mi.F32, "grouped"),
+    (1100, 256, 384, 4, 3, mi.BF16, mi.BF16, "grouped")])
+def test_ffn_tokens_reads_rows_through_perm(moe, T, d, f, E, k, wdt, xdt, path_name):
+    """moe_expert_ffn_tokens (rows read as x[perm[i] / k], no gathered copy) gives the bits of
+    moe_expert_ffn on the gathered rows, in every kernel family, and matches the oracle."""
+    cfg = mi.small_config("tok", T, d, f, E, k, 2300 + T + d, w_dtype=wdt, x_dtype=xdt, zipf_s=1.2)
+    li = mi.make_layer(cfg, threads=1)
+    W = pack_layer(li)
+    want = {"fp32": moe.MOE_FFN_AUTO, "stream": moe.MOE_FFN_STREAM, "mid": moe.MOE_FFN_MID,
+            "grouped": moe.MOE_FFN_GROUPED}[path_name]
+    got = moe.moe_expert_ffn_plan(cfg.N, E, d, f, moe.MOE_F32 if wdt == mi.F32 else moe.MOE_BF16)
+    assert got["path"] == want
+    x = to_dev(li.x)
+    idx, w = moe.moe_route(to_dev(li.logits), k)
+    counts, offsets, perm, inv_perm, none = moe.moe_permute(idx, E, None)   # indices only
+    assert none is None
+    yg = torch.full((cfg.N, d), float("nan"), device="cuda")
+    moe.moe_expert_ffn_tokens(W, x, k, perm, offsets, yg=yg)
+    _, _, _, _, xg = moe.moe_permute(idx, E, x)
+    ref_gpu = moe.moe_expert_ffn(W, xg, offsets)
+    assert torch.equal(yg, ref_gpu)
+    ref = orc.layer(mi.to_f64(li.x), li.logits, li.w1, li.w3, li.w2, k)
+    assert max_rel(to_host(yg), ref["yg"]) <= (TOL_F32 if wdt == mi.F32 else TOL_BF16)
+    y = moe.moe_combine(yg, inv_perm, w)
+    assert max_rel(to_host(y), ref["y"]) <= (TOL_F32 if wdt == mi.F32 else TOL_BF16)
+    W.free()
+
+
 def test_ffn_rejects_short_workspace_and_bad_path(moe):
     cfg = mi.small_config("ws", 4, 256, 512, 8, 2, 9, w_dtype=mi.BF16)
     li = mi.make_layer(cfg, threads=1)
