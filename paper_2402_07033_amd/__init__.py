@@ -5,7 +5,9 @@ Every step runs in hand-written HIP kernels; PyTorch only provides device
 memory and streams.  There is no CPU fallback: importing the binding's
 functions without the built library raises.
 """
-from .binding import (MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID,
+from .binding import (ORCH_CPU, ORCH_GPU_RESIDENT, ORCH_GPU_TRANSFER, ORCH_SKIP, OrchLayer,
+                      moe_orch_cpu_expert_ffn, moe_orch_decide, moe_orch_hit_rate, moe_orch_place,
+                      MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_MID,
                       MOE_FFN_STREAM, MoeError, PackedWeights, StackBuffers, lib, lib_path,
                       moe_combine, moe_combine_norm_route_permute, moe_combine_parts,
                       moe_combine_residual, moe_decode_layer, moe_expert_ffn,
@@ -18,6 +20,8 @@ from .binding import (MOE_BF16, MOE_F32, MOE_FFN_AUTO, MOE_FFN_GROUPED, MOE_FFN_
                       moe_status_string, moe_weights_free, moe_weights_pack)
 
 __all__ = [
+    "ORCH_CPU", "ORCH_GPU_RESIDENT", "ORCH_GPU_TRANSFER", "ORCH_SKIP", "OrchLayer",
+    "moe_orch_cpu_expert_ffn", "moe_orch_decide", "moe_orch_hit_rate", "moe_orch_place",
     "MOE_BF16", "MOE_F32", "MOE_FFN_AUTO", "MOE_FFN_GROUPED", "MOE_FFN_MID", "MOE_FFN_STREAM",
     "MoeError", "PackedWeights", "StackBuffers", "lib", "lib_path", "moe_combine",
     "moe_combine_norm_route_permute", "moe_combine_parts", "moe_combine_residual",

@@ -26,6 +26,16 @@ EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_norm_route_permute", "moe_combine_residual", "moe_combine_norm_route_permute",
            "moe_rmsnorm_router_logits")
 PROBE_EXPORTS = ("moe_set_ffn_mid_event", "moe_mfma_rate_probe", "moe_hbm_read_probe")
+ORCH_EXPORTS = ("moe_orch_place", "moe_orch_hit_rate", "moe_orch_decide", "moe_orch_cpu_expert_ffn",
+                "moe_orch_layer_create", "moe_orch_layer_free", "moe_orch_calibrate",
+                "moe_orch_expert_ffn")
+ORCH_SKIP, ORCH_GPU_RESIDENT, ORCH_GPU_TRANSFER, ORCH_CPU = 0, 1, 2, 3
+
+
+class OrchLatency(C.Structure):
+    """moe_orch_latency_t."""
+    _fields_ = [("gpu_lat_us", C.c_double), ("cpu_lat_us_per_row", C.c_double),
+                ("transfer_lat_us", C.c_double)]
 
 
 class FfnPlan(C.Structure):
@@ -103,6 +113,21 @@ def lib():
         L.moe_combine_parts.restype = C.c_int
         L.moe_decode_layer.argtypes = [vp, vp, vp, i32, i32] + [vp] * 8 + [C.c_size_t, vp, vp, vp]
         L.moe_decode_layer.restype = C.c_int
+        dp = C.POINTER(C.c_double)
+        L.moe_orch_place.argtypes = [vp, i32, i32, i32, vp]
+        L.moe_orch_hit_rate.argtypes = [vp, vp, i32, i32]
+        L.moe_orch_hit_rate.restype = C.c_double
+        L.moe_orch_decide.argtypes = [vp, vp, i32, C.POINTER(OrchLatency), vp]
+        L.moe_orch_cpu_expert_ffn.argtypes = [vp, i32, vp, vp, vp, i32, i32, vp]
+        L.moe_orch_layer_create.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, C.POINTER(vp), vp]
+        L.moe_orch_layer_free.argtypes = [vp]
+        L.moe_orch_calibrate.argtypes = [vp, vp, C.c_size_t, C.POINTER(OrchLatency), vp]
+        L.moe_orch_expert_ffn.argtypes = [vp, C.POINTER(OrchLatency), vp, vp, i32, vp, C.c_size_t,
+                                          vp, vp, vp]
+        for n in ORCH_EXPORTS:
+            if n != "moe_orch_hit_rate":
+                getattr(L, n).restype = C.c_int
+        del dp
         for n in ("moe_route", "moe_permute", "moe_weights_pack", "moe_weights_free",
                   "moe_expert_ffn", "moe_expert_ffn_path", "moe_combine", "moe_rmsnorm",
                   "moe_router_logits", "moe_residual_add", "moe_set_ffn_mid_event",
@@ -622,3 +647,109 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
     if cur is not x:
         x.copy_(cur)
     return x
+
+
+# ---- the paper's own method over the expert kernels (include/moe_orch.h) ----------------
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def moe_orch_place(popularity, capacity: int):
+    """popularity [L,E] (numpy, host) -> at_gpu uint8 [L,E]: the `capacity` most popular."""
+    import numpy as np
+    pop = np.ascontiguousarray(popularity, dtype=np.float64)
+    L, E = pop.shape
+    at_gpu = np.zeros((L, E), dtype=np.uint8)
+    _check(lib().moe_orch_place(_np_ptr(pop), L, E, capacity, _np_ptr(at_gpu)), "moe_orch_place")
+    return at_gpu
+
+
+def moe_orch_hit_rate(popularity, at_gpu) -> float:
+    import numpy as np
+    pop = np.ascontiguousarray(popularity, dtype=np.float64)
+    ag = np.ascontiguousarray(at_gpu, dtype=np.uint8)
+    L, E = pop.shape
+    return float(lib().moe_orch_hit_rate(_np_ptr(pop), _np_ptr(ag), L, E))
+
+
+def _latency(lat) -> OrchLatency:
+    if isinstance(lat, OrchLatency):
+        return lat
+    return OrchLatency(lat["gpu_lat_us"], lat["cpu_lat_us_per_row"], lat["transfer_lat_us"])
+
+
+def moe_orch_decide(at_gpu_layer, inp_size, lat):
+    """Algorithm 1 for one layer (host arrays) -> int32 [E] of ORCH_* decisions."""
+    import numpy as np
+    ag = np.ascontiguousarray(at_gpu_layer, dtype=np.uint8)
+    sz = np.ascontiguousarray(inp_size, dtype=np.int32)
+    out = np.zeros(sz.shape[0], dtype=np.int32)
+    cl = _latency(lat)
+    _check(lib().moe_orch_decide(_np_ptr(ag), _np_ptr(sz), sz.shape[0], C.byref(cl), _np_ptr(out)),
+           "moe_orch_decide")
+    return out
+
+
+def moe_orch_cpu_expert_ffn(x, w1, w3, w2):
+    """Host-side expert: x fp32 [s,d], w1/w3 [d,f], w2 [f,d] bf16 bits (uint16) -> y fp32 [s,d]."""
+    import numpy as np
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    w1, w3, w2 = (np.ascontiguousarray(w, dtype=np.uint16) for w in (w1, w3, w2))
+    s, d = x.shape
+    f = w1.shape[1]
+    y = np.zeros((s, d), dtype=np.float32)
+    _check(lib().moe_orch_cpu_expert_ffn(_np_ptr(x), s, _np_ptr(w1), _np_ptr(w3), _np_ptr(w2), d, f,
+                                         _np_ptr(y)), "moe_orch_cpu_expert_ffn")
+    return y
+
+
+class OrchLayer:
+    """Owner of a moe_orch_layer_t handle: a layer split between device and host memory."""
+
+    def __init__(self, w1, w3, w2, at_gpu, max_rows: int, stream=None):
+        import numpy as np
+        w1, w3, w2 = (np.ascontiguousarray(w, dtype=np.uint16) for w in (w1, w3, w2))
+        self.E, self.d, self.f = w1.shape
+        ag = np.ascontiguousarray(at_gpu, dtype=np.uint8)
+        h = C.c_void_p()
+        _check(lib().moe_orch_layer_create(_np_ptr(w1), _np_ptr(w3), _np_ptr(w2), self.E, self.d,
+                                           self.f, _np_ptr(ag), max_rows, C.byref(h),
+                                           _stream(stream)), "moe_orch_layer_create")
+        self.handle, self.max_rows = h.value, max_rows
+        self.ws = torch.empty(max(moe_expert_ffn_workspace(max_rows, 1, self.d, self.f, MOE_F32), 256),
+                              dtype=torch.uint8, device="cuda")
+
+    def calibrate(self, stream=None) -> dict:
+        cl = OrchLatency()
+        _check(lib().moe_orch_calibrate(C.c_void_p(self.handle), _ptr(self.ws), self.ws.numel(),
+                                        C.byref(cl), _stream(stream)), "moe_orch_calibrate")
+        return dict(gpu_lat_us=cl.gpu_lat_us, cpu_lat_us_per_row=cl.cpu_lat_us_per_row,
+                    transfer_lat_us=cl.transfer_lat_us)
+
+    def expert_ffn(self, lat, xg: torch.Tensor, offsets: torch.Tensor, yg=None, stream=None):
+        """-> (yg fp32 [N,d], decisions int32 [E] as Algorithm 1 chose them)."""
+        import numpy as np
+        _dev(xg, torch.float32, "xg")
+        _dev(offsets, torch.int32, "offsets")
+        N = xg.shape[0]
+        if yg is None:
+            yg = torch.empty((N, self.d), dtype=torch.float32, device=xg.device)
+        dec = np.zeros(self.E, dtype=np.int32)
+        cl = _latency(lat)
+        _check(lib().moe_orch_expert_ffn(C.c_void_p(self.handle), C.byref(cl), _ptr(xg),
+                                         _ptr(offsets), N, _ptr(self.ws), self.ws.numel(),
+                                         _ptr(yg), _np_ptr(dec), _stream(stream)),
+               "moe_orch_expert_ffn")
+        return yg, dec
+
+    def free(self):
+        if self.handle:
+            h, self.handle = self.handle, 0
+            _check(lib().moe_orch_layer_free(C.c_void_p(h)), "moe_orch_layer_free")
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass

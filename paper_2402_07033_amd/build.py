@@ -13,7 +13,7 @@ OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libmoe_hip.so")
 SOURCES = ["moe_api.hip", "moe_route_permute.hip", "moe_weights.hip", "moe_ffn_f32.hip",
            "moe_ffn_stream.hip", "moe_ffn_grouped.hip", "moe_ffn_mid.hip", "moe_probe.hip",
-           "moe_noalloc.hip"]
+           "moe_noalloc.hip", "moe_orch.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

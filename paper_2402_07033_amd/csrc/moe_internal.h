@@ -132,6 +132,8 @@ int moe_norm_logits_launch(bool norm, const float* x, const float* w_gate, int T
 int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E, int d, int f,
                           moe_dtype_t w_dtype, moe_weights** out, hipStream_t s);
 int moe_weights_free_impl(moe_weights* W);
+int moe_weights_repack_impl(moe_weights* W, const void* w1, const void* w3, const void* w2,
+                            hipStream_t s);
 int moe_gate_small_launch(bool norm, const float* x, const float* w_gate, const float* logits_in,
                           int T, int d, int E, int k, float eps, float* h_out, float* logits_out,
                           int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,

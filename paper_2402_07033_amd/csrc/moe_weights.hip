@@ -125,6 +125,21 @@ int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E,
     return MOE_OK;
 }
 
+// Repack into the buffers of an existing bf16 handle of the same shape (no allocation): the
+// staging slot of the split-layer execution.  Sources are device arrays.
+int moe_weights_repack_impl(moe_weights* W, const void* w1, const void* w3, const void* w2,
+                            hipStream_t s) {
+    if (!W || W->dtype != MOE_BF16 || !W->w13 || !W->w2) return MOE_ERR_INVALID_ARG;
+    const unsigned grid = 8192;
+    hipLaunchKernelGGL(pack_frag_kernel, dim3(grid), dim3(256), 0, s, (const uint16_t*)w1,
+                       (uint4*)W->w13, W->E, W->d, W->f, 2, 0);
+    hipLaunchKernelGGL(pack_frag_kernel, dim3(grid), dim3(256), 0, s, (const uint16_t*)w3,
+                       (uint4*)W->w13, W->E, W->d, W->f, 2, 1);
+    hipLaunchKernelGGL(pack_frag_kernel, dim3(grid), dim3(256), 0, s, (const uint16_t*)w2,
+                       (uint4*)W->w2, W->E, W->f, W->d, 1, 0);
+    return moe_launch_status();
+}
+
 int moe_weights_free_impl(moe_weights* W) {
     if (!W) return MOE_OK;
     int rc = MOE_OK;

@@ -34,8 +34,12 @@ def test_header_symbols_are_exported(L):
         assert hasattr(L, n), f"{n} declared under include/ but not exported"
     assert sorted(binding.EXPORTS) == names
     assert sorted(binding.PROBE_EXPORTS) == probes
-    # the measurement probes are not declared in the layer's header
-    assert not set(names) & set(probes)
+    orch = _declared_functions("moe_orch.h")
+    for n in orch:
+        assert hasattr(L, n), f"{n} declared in include/moe_orch.h but not exported"
+    assert sorted(binding.ORCH_EXPORTS) == orch
+    # the measurement probes and the split-layer calls are not declared in the layer's header
+    assert not set(names) & set(probes) and not set(names) & set(orch)
 
 
 def test_status_strings(L):
