@@ -20,5 +20,24 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+CHECK_SRC = os.path.join(HERE, "sanitize_check.c")
+CHECK_EXE = os.path.join(HERE, "sanitize_check")
+
+
+def build_sanitize_check(sanitize: bool = True) -> str:
+    """The oracle and its small driver (sanitize_check.c) as one executable under
+    -fsanitize=address,undefined (static runtimes: another preloaded library must not come
+    before them).  sanitize=False builds the same program plainly."""
+    exe = CHECK_EXE + ("" if sanitize else "_plain")
+    tmp = exe + f".tmp{os.getpid()}"
+    flags = (["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+              "-static-libubsan", "-fno-omit-frame-pointer", "-g"] if sanitize else [])
+    cmd = ["gcc", "-O1", "-std=c11", "-Wall", "-Wextra", "-Wno-unknown-pragmas", *flags, "-o", tmp, CHECK_SRC, SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, exe)
+    return exe
+
+
 if __name__ == "__main__":
     print(build(force=True))
+    print(build_sanitize_check())

@@ -290,7 +290,7 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
         return (const u32x4_t*)((const char*)p + voff);
     };
     // g = running step count of this workgroup (never reset): LDS stage g % NS
-    auto issue_b = [&](int i, int j, int gstage) {
+    auto issue_b = [&](int i, int j, unsigned gstage) {
         __builtin_amdgcn_global_load_lds(
             (const __attribute__((address_space(1))) void*)b_src(i, j),
             (__attribute__((address_space(3))) void*)(lds + ((gstage % NS) * NBW + NBQ * wave + i) * 64),
@@ -315,7 +315,7 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
     for (int i = 0; i < NBW; i++) breg[i] = __builtin_bit_cast(bf16x8_t, lds[i * 64 + lane]);
     GG_WAIT_LGKM(0);
 
-    int g = 0;  // running step count
+    unsigned g = 0;  // running step count (unsigned: g % NS is a mask for the 8-stage ring)
     for (;;) {
 #pragma unroll
         for (int i = 0; i < NBW; i++)

@@ -349,3 +349,18 @@ def test_stack_is_norm_route_layer_residual():
     # forcing the oracle's own logits changes nothing
     forced = orc.stack(x0, layers, k, forced_logits=out["logits"])
     assert (forced["x"] == out["x"]).all()
+
+
+# ------------------------------------------------- sanitizer run of the oracle ----
+
+def test_oracle_is_clean_under_address_and_undefined_sanitizers():
+    """The oracle's C source, driven over small layers with the edge cases (an empty expert,
+    k == E, no tokens, both weight dtypes), built with -fsanitize=address,undefined: the run
+    must finish without a report and print what the plain build of the same program prints."""
+    import subprocess
+    from oracle import build
+    san = subprocess.run([build.build_sanitize_check(True)], capture_output=True, text=True, timeout=120)
+    plain = subprocess.run([build.build_sanitize_check(False)], capture_output=True, text=True, timeout=120)
+    assert san.returncode == 0 and plain.returncode == 0, san.stderr[-2000:]
+    assert "ERROR" not in san.stderr and "runtime error" not in san.stderr, san.stderr[-2000:]
+    assert san.stdout == plain.stdout and san.stdout.count("rc=0") == 4
