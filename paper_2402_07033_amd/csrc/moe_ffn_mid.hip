@@ -446,10 +446,10 @@ int moe_ffn_mid_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dty
     }
 
     if (act_dtype == MOE_BF16)
-        hipLaunchKernelGGL(gg_pack_kernel<true>, dim3((unsigned)nb), dim3(256), 0, s, xg, perm, k,
+        hipLaunchKernelGGL(gg_pack_kernel<true>, gg_pack_grid(nb, d), dim3(256), 0, s, xg, perm, k,
                            offsets, E, N, d, xp);
     else
-        hipLaunchKernelGGL(gg_pack_kernel<false>, dim3((unsigned)nb), dim3(256), 0, s, xg, perm, k,
+        hipLaunchKernelGGL(gg_pack_kernel<false>, gg_pack_grid(nb, d), dim3(256), 0, s, xg, perm, k,
                            offsets, E, N, d, xp);
 
     float* part = (float*)((unsigned char*)ws + md_align256(nb * 16 * d * 2) + md_align256(nb * 16 * f * 2));

@@ -36,10 +36,12 @@ __device__ __forceinline__ bool gg_find_block(const int32_t* __restrict__ offset
 }
 
 // ------------------------------------------------------------------- pack ----
-// One workgroup per packed block: rows [row0 + 16*b, +16) of a segment become
-// d/32 B-operand fragments; rows past the segment end are zero.  With `perm` the batched
-// row i is read as xg[perm[i] / k]: xg is then the token array itself and the gathered copy
-// is never materialised.
+// blockIdx.x = packed block: rows [row0 + 16*b, +16) of a segment become d/32 B-operand
+// fragments; rows past the segment end are zero.  blockIdx.y splits the block's fragments
+// into ranges of GG_PACK_KS reduction steps, so that a launch with few blocks (a few hundred
+// rows) still fills the chip.  With `perm` the batched row i is read as xg[perm[i] / k]: xg
+// is then the token array itself and the gathered copy is never materialised.
+#define GG_PACK_KS 32
 template <bool ACT_BF16>
 __global__ __launch_bounds__(256) void gg_pack_kernel(const void* __restrict__ xg,
                                                       const int32_t* __restrict__ perm, int k,
@@ -49,13 +51,18 @@ __global__ __launch_bounds__(256) void gg_pack_kernel(const void* __restrict__ x
     if (!gg_find_block(offsets, E, N, blockIdx.x, si)) return;
     const int b = blockIdx.x - si.bbase;
     const int KS = d / 32;
-    for (int i = threadIdx.x; i < KS * 64; i += 256) {
-        const int lane = i & 63, ks = i >> 6;
-        const int t = lane & 15, kq = lane >> 4;
-        const int r = b * 16 + t;
+    const int ks_lo = blockIdx.y * GG_PACK_KS;
+    const int ks_n = (KS - ks_lo) < GG_PACK_KS ? (KS - ks_lo) : GG_PACK_KS;
+    // the lane's source row is the same for every fragment of the block
+    const int t = threadIdx.x & 15;
+    const int r = b * 16 + t;
+    int src = si.row0 + r;
+    if (perm && r < si.rows) src = perm[si.row0 + r] / k;
+    for (int i = threadIdx.x; i < ks_n * 64; i += 256) {
+        const int lane = i & 63, ks = ks_lo + (i >> 6);
+        const int kq = lane >> 4;
         u32x4_t v = {0u, 0u, 0u, 0u};
         if (r < si.rows) {
-            const int src = perm ? perm[si.row0 + r] / k : si.row0 + r;
             const size_t off = (size_t)src * d + (size_t)ks * 32 + kq * 8;
             if (ACT_BF16) {
                 v = *(const u32x4_t*)((const uint16_t*)xg + off);
@@ -72,3 +79,7 @@ __global__ __launch_bounds__(256) void gg_pack_kernel(const void* __restrict__ x
     }
 }
 
+// grid of gg_pack_kernel for `nb` packed blocks of d columns
+static inline dim3 gg_pack_grid(size_t nb, int d) {
+    return dim3((unsigned)nb, (unsigned)((d / 32 + GG_PACK_KS - 1) / GG_PACK_KS));
+}
