@@ -14,9 +14,10 @@
 //           hp [block][f/32] for the second GEMM
 //   down  : per (token tile of 256 rows, 256 output features): yg = h.w2, fp32
 //
-// GEMM kernel (measured limits that shaped it: LDS reads 128 B/clk per CU,
-// vector-memory path ~50-64 B/clk per CU, one 256 x 256 x 32 step = 1024
-// matrix-core clocks per SIMD):
+// GEMM kernel (measured figures behind it: one 256 x 256 x 32 step = 1024 matrix-core
+// clocks per SIMD; four waves read ~140 B/clk from LDS and pull ~60 B/clk of L2-resident
+// data per CU, more with more waves; the operand stream of this tile is 31 B/clk at the
+// full matrix rate, 29 % of which misses L2):
 //   * workgroup tile 256 tokens x 16 weight fragment rows, 4 waves, one per
 //     SIMD; wave w owns fragment rows 4w..4w+3 for ALL 16 token blocks:
 //     64 MFMA tiles = 256 accumulator registers (pinned to the accumulation
