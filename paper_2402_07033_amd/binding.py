@@ -558,7 +558,10 @@ class StackBuffers:
         self.ws = torch.empty(max(moe_expert_ffn_workspace(N, E, d, f, MOE_F32), 256),
                               dtype=torch.uint8, device=device)
         # the second projection's reduction parts (decode kernels; slab 0 is yg otherwise)
-        plan = moe_expert_ffn_plan(N, E, d, f, MOE_BF16)
+        try:
+            plan = moe_expert_ffn_plan(N, E, d, f, MOE_BF16)
+        except MoeError:   # a shape only the fp32 kernels serve
+            plan = dict(n_parts=1, path=MOE_FFN_STREAM)
         self.max_parts = max(1, plan["n_parts"])
         # prefill-sized passes read the normalised rows through perm: no gathered copy
         self.rows_through_perm = plan["path"] != MOE_FFN_STREAM
