@@ -177,7 +177,7 @@ int moe_expert_ffn_plan(int N, int E, int d, int f, moe_dtype_t w_dtype, int pat
     plan->path = path;
     if (path == MOE_FFN_STREAM) {
         if (!moe_ffn_stream_supported(d, f)) return MOE_ERR_UNSUPPORTED;
-        plan->n_parts = moe_ffn_stream_parts(d, f);
+        plan->n_parts = moe_ffn_stream_parts(N, d, f);
     } else if (path == MOE_FFN_MID) {
         if (!moe_ffn_mid_supported(N, E, d, f)) return MOE_ERR_UNSUPPORTED;
     } else {
@@ -199,7 +199,7 @@ int moe_expert_ffn_parts(const moe_weights_t* W, const void* xg, moe_dtype_t act
     if (act_dtype != MOE_F32 && act_dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
     if (!offsets || !xg || !yg_parts || !moe_aligned16(xg) || !moe_aligned16(yg_parts))
         return MOE_ERR_INVALID_ARG;
-    if (moe_ffn_stream_parts(W->d, W->f) > max_parts) return MOE_ERR_INVALID_ARG;
+    if (moe_ffn_stream_parts(N, W->d, W->f) > max_parts) return MOE_ERR_INVALID_ARG;
     if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
     if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, act_dtype))
         return MOE_ERR_WORKSPACE;
@@ -251,9 +251,9 @@ int moe_decode_layer(const moe_weights_t* W, const float* x, const float* logits
     int n_parts = 1;
     size_t stride = 0;
     int rc = moe_ffn_stream_decode_launch(W, x, logits, T, k, idx, weights, counts, offsets, perm,
-                                          inv_perm, xg, workspace, &parts, &n_parts, &stride,
+                                          inv_perm, xg, workspace, y, yg, &parts, &n_parts, &stride,
                                           (hipStream_t)stream);
-    if (rc != MOE_OK) return rc;
+    if (rc != MOE_OK || n_parts == 0) return rc;  // 0 parts: the second kernel combined already
     return moe_combine_parts_launch(parts, n_parts, stride, inv_perm, weights, T, k, W->d, y, false,
                                     yg, (hipStream_t)stream);
 }

@@ -322,6 +322,197 @@ __global__ __launch_bounds__(256) void stream_reduce_kernel(const float4* __rest
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Second projection for one to four routed rows (one or two tokens' worth: the single-batch
+// decode step of Sec. 4.1, scenario (a)): one workgroup per block of 16 output features
+// streams that block's whole reduction for every row, so the sum over f is finished inside
+// the workgroup -- no slabs, no second pass -- and the gate-weighted combine of the rows
+// (Sec. 3.2: the layer's output is the gate-weighted sum of the selected experts' outputs)
+// is done on the spot.  The rows of h, split into bf16 high and low halves, sit in LDS; a
+// wave owns one row and a contiguous share of its reduction steps and keeps 16 fragment
+// loads in flight.  The sums are added in a fixed order: the result is deterministic.
+#define SM_MAX_ROWS 4
+#define SM_WAVES 8
+#define SM_RING 16
+#define SM_STAGE_ITERS 8   // h groups (of 8 floats) per thread, at most
+
+struct SmallDownArgs {
+    const u32x4_t* wfrag;     // w2 fragments [E][NB][KS]
+    const float* h;           // [N,K] fp32
+    const int32_t* offsets;   // [E+1]
+    const int32_t* inv_perm;  // [T*k], or null: no combine
+    const float* weights;     // [T,k]
+    float* y;                 // [T,C] out (with inv_perm)
+    float* yg;                // [N,C] out, or null
+    int E, N, K, C, NB, KS, T, k;
+};
+
+__global__ __launch_bounds__(64 * SM_WAVES) void stream_down_small_kernel(SmallDownArgs a) {
+    extern __shared__ __align__(16) unsigned char sm_raw[];
+    // [N*KS*4] groups of {hi 16 B, lo 16 B}, then 32 B of zeros, then the waves' partial tiles
+    u32x4_t* s_h = (u32x4_t*)sm_raw;
+    const int n_groups = a.N * a.KS * 4;
+    u32x4_t* s_zero = s_h + 2 * (size_t)n_groups;
+    f32x4_t* s_red = (f32x4_t*)(s_zero + 2);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nb = blockIdx.x;
+
+    // h first (its loads are the oldest, so the wait for them does not include the weights)
+    float4 hv[SM_STAGE_ITERS][2];
+#pragma unroll
+    for (int i = 0; i < SM_STAGE_ITERS; i++) {
+        const int g = tid + i * 64 * SM_WAVES;
+        if (g < n_groups) {
+            hv[i][0] = *(const float4*)(a.h + (size_t)g * 8);
+            hv[i][1] = *(const float4*)(a.h + (size_t)g * 8 + 4);
+        }
+    }
+
+    // this wave's row and share of its reduction steps
+    const int wpr = SM_WAVES / a.N;  // waves per row
+    const int r = wave / wpr, sub = wave % wpr;
+    const int chunk = (a.KS + wpr - 1) / wpr;
+    int ks0 = sub * chunk, S = 0;
+    int e = 0;
+    if (r < a.N) {
+        const int ks1 = (ks0 + chunk) < a.KS ? (ks0 + chunk) : a.KS;
+        S = ks1 > ks0 ? ks1 - ks0 : 0;
+        int lo = 0, hi = 0;
+        if (lane < a.E) {
+            lo = a.offsets[lane];
+            hi = a.offsets[lane + 1];
+        }
+        const unsigned long long m = __ballot(lane < a.E && lo <= r && r < hi);
+        if (m == 0ull) S = 0;  // offsets that do not cover the row: nothing is read
+        e = __builtin_amdgcn_readfirstlane(m ? (int)__builtin_ctzll(m) : 0);
+    }
+    S = __builtin_amdgcn_readfirstlane(S);
+    const u32x4_t* wsrc = a.wfrag + (((size_t)e * a.NB + nb) * a.KS + ks0) * 64 + lane;
+    u32x4_t buf[SM_RING];
+    if (S > 0) {
+#pragma unroll
+        for (int i = 0; i < SM_RING; i++) {
+            const int st = i < S ? i : S - 1;
+            buf[i] = __builtin_nontemporal_load(wsrc + (size_t)st * 64);
+        }
+    }
+
+    // stage h: bf16 high and low halves, in the matrix cores' operand order
+#pragma unroll
+    for (int i = 0; i < SM_STAGE_ITERS; i++) {
+        const int g = tid + i * 64 * SM_WAVES;
+        if (g < n_groups) {
+            const float x[8] = {hv[i][0].x, hv[i][0].y, hv[i][0].z, hv[i][0].w,
+                                hv[i][1].x, hv[i][1].y, hv[i][1].z, hv[i][1].w};
+            unsigned hi[8], lo[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                hi[j] = moe_bf16_rne(x[j]);
+                lo[j] = moe_bf16_rne(x[j] - moe_bf16_to_f32(hi[j]));
+            }
+            s_h[2 * g] = u32x4_t{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),
+                                 hi[6] | (hi[7] << 16)};
+            s_h[2 * g + 1] = u32x4_t{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16),
+                                     lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
+        }
+    }
+    if (tid < 2) s_zero[tid] = u32x4_t{0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    // B operand: column 0 carries the row, the other 15 columns are zero
+    const int t = lane & 15, kq = lane >> 4;
+    const u32x4_t* bsrc = (t == 0) ? s_h + 2 * (((size_t)r * a.KS + ks0) * 4 + kq) : s_zero;
+    const int bstep = (t == 0) ? 8 : 0;  // u32x4 per reduction step
+    f32x4_t acc_hi = {0.f, 0.f, 0.f, 0.f}, acc_lo = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0; base < S; base += SM_RING) {
+#pragma unroll
+        for (int i = 0; i < SM_RING; i++) {
+            const int st = base + i;
+            if (st < S) {
+                const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, buf[i]);
+                const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, bsrc[(size_t)st * bstep]);
+                const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, bsrc[(size_t)st * bstep + 1]);
+                acc_hi = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, bh, acc_hi, 0, 0, 0);
+                acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, bl, acc_lo, 0, 0, 0);
+                if (st + SM_RING < S)
+                    buf[i] = __builtin_nontemporal_load(wsrc + (size_t)(st + SM_RING) * 64);
+            }
+        }
+    }
+    s_red[wave * 64 + lane] = acc_hi + acc_lo;
+    __syncthreads();
+
+    // lanes 0, 16, 32, 48 of wave 0 hold features 4*kq .. 4*kq+3 of column 0
+    if (wave != 0 || t != 0) return;
+    auto row_sum = [&](int row) -> float4 {
+        f32x4_t v = s_red[(row * wpr) * 64 + lane];
+        for (int w = 1; w < wpr; w++) v += s_red[(row * wpr + w) * 64 + lane];
+        return make_float4(v[0], v[1], v[2], v[3]);
+    };
+    const size_t col = (size_t)nb * 16 + 4 * kq;
+    if (a.yg)
+        for (int row = 0; row < a.N; row++) *(float4*)(a.yg + (size_t)row * a.C + col) = row_sum(row);
+    if (a.inv_perm) {
+        for (int tok = 0; tok < a.T; tok++) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j = 0; j < a.k; j++) {
+                const float w = a.weights[tok * a.k + j];
+                int row = a.inv_perm[tok * a.k + j];
+                row = row < 0 ? 0 : (row >= a.N ? a.N - 1 : row);
+                const float4 v = row_sum(row);
+                acc.x += w * v.x;
+                acc.y += w * v.y;
+                acc.z += w * v.z;
+                acc.w += w * v.w;
+            }
+            *(float4*)(a.y + (size_t)tok * a.C + col) = acc;
+        }
+    }
+}
+
+static size_t small_down_lds(int N, int KS) {
+    return (size_t)N * KS * 4 * 32 + 32 + (size_t)SM_WAVES * 64 * sizeof(f32x4_t);
+}
+
+// The small-row kernel serves a call when its rows fit in LDS and one workgroup per feature
+// block fills the chip no worse than one round of it.
+static bool small_down_ok(int N, int d, int f) {
+    if (N < 1 || N > SM_MAX_ROWS) return false;
+    const int KS = f / 32, NB = d / 16;
+    if (f % 32 || d % 16) return false;
+    if ((long long)N * KS * 4 > (long long)SM_STAGE_ITERS * 64 * SM_WAVES) return false;
+    if (small_down_lds(N, KS) > 160 * 1024) return false;
+    return NB <= moe_num_cus();
+}
+
+static int small_down_launch(const moe_weights* W, const float* h, const int32_t* offsets, int N,
+                             const int32_t* inv_perm, const float* weights, int T, int k, float* y,
+                             float* yg, hipStream_t s) {
+    SmallDownArgs a = {};
+    a.wfrag = (const u32x4_t*)W->w2;
+    a.h = h;
+    a.offsets = offsets;
+    a.inv_perm = inv_perm;
+    a.weights = weights;
+    a.y = y;
+    a.yg = yg;
+    a.E = W->E; a.N = N; a.K = W->f; a.C = W->d; a.NB = W->d / 16; a.KS = W->f / 32;
+    a.T = T; a.k = k;
+    const size_t lds = small_down_lds(N, a.KS);
+    static std::atomic<bool> attr_set[MOE_MAX_DEVICES];
+    const int dev = moe_current_device();
+    if (dev < 0) return MOE_ERR_HIP;
+    if (!attr_set[dev].load(std::memory_order_relaxed)) {
+        MOE_HIP_TRY(hipFuncSetAttribute((const void*)stream_down_small_kernel,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set[dev].store(true, std::memory_order_relaxed);
+    }
+    hipLaunchKernelGGL(stream_down_small_kernel, dim3((unsigned)a.NB), dim3(64 * SM_WAVES), lds, s, a);
+    return moe_launch_status();
+}
+
 // Split a reduction of KS steps (of 32) into P parts x W waves x KSW steps.
 static bool stream_pick(int KS, bool allow_parts, int& W, int& KSW, int& P) {
     int best = -1;
@@ -437,14 +628,15 @@ static StreamArgs stream_args_down(const moe_weights* W, const StreamPlan& pl, c
     return dn;
 }
 
-int moe_ffn_stream_parts(int d, int f) {
+int moe_ffn_stream_parts(int N, int d, int f) {
     StreamPlan pl;
-    return stream_plan(d, f, pl) ? pl.Pd : 0;
+    if (!stream_plan(d, f, pl)) return 0;
+    return small_down_ok(N, d, f) ? 1 : pl.Pd;
 }
 
 // n_parts == null: `out` is yg [N,d]; the slabs of a split reduction go to the workspace and
-// are added by a third launch.  Else `out` holds moe_ffn_stream_parts(d, f) slabs [N,d] that
-// are left for the caller to add, and *n_parts receives their number.
+// are added by a third launch.  Else `out` holds moe_ffn_stream_parts(N, d, f) slabs [N,d]
+// that are left for the caller to add, and *n_parts receives their number.
 int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
                           const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
                           float* out, int* n_parts, hipStream_t s) {
@@ -461,6 +653,10 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
                                      : stream_dispatch<2, false, false>(pl.KSWu, pl.Wu, s, up);
     if (rc != MOE_OK) return rc;
     moe_record_mid_event(s);
+    if (small_down_ok(N, d, f)) {
+        if (n_parts) *n_parts = 1;
+        return small_down_launch(W, h, offsets, N, nullptr, nullptr, 0, 0, nullptr, out, s);
+    }
     const StreamArgs dn = stream_args_down(W, pl, h, offsets, N, pl.Pd > 1 ? slabs : out);
     rc = stream_dispatch<1, false, false>(pl.KSWd, pl.Wd, s, dn);
     if (n_parts) *n_parts = pl.Pd;
@@ -480,13 +676,15 @@ bool moe_ffn_stream_decode_supported(int T, int E, int k, int d, int f) {
 }
 
 // Both projections of a decode step with the gating function and the per-expert batching in
-// the first kernel's prologue.  The second projection's result stays in *n_parts slabs of
-// [T*k, d] floats at *parts, *part_stride floats apart, for the caller's combine to add.
+// the first kernel's prologue.  With one to four routed rows the second kernel also does the
+// gate-weighted combine: y (and yg, if not null) are written and *n_parts is 0.  Otherwise
+// the second projection's result stays in *n_parts slabs of [T*k, d] floats at *parts,
+// *part_stride floats apart, for the caller's combine to add.
 int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const float* logits, int T,
                                  int k, int32_t* idx, float* weights, int32_t* counts,
                                  int32_t* offsets, int32_t* perm, int32_t* inv_perm, float* xg,
-                                 void* ws, const float** parts, int* n_parts, size_t* part_stride,
-                                 hipStream_t s) {
+                                 void* ws, float* y, float* yg, const float** parts, int* n_parts,
+                                 size_t* part_stride, hipStream_t s) {
     const int d = W->d, f = W->f, E = W->E, N = T * k;
     StreamPlan pl;
     if (!moe_ffn_stream_decode_supported(T, E, k, d, f) || !stream_plan(d, f, pl))
@@ -507,6 +705,12 @@ int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const flo
     int rc = stream_dispatch<2, false, true>(pl.KSWu, pl.Wu, s, up);
     if (rc != MOE_OK) return rc;
     moe_record_mid_event(s);
+    if (small_down_ok(N, d, f)) {
+        *parts = nullptr;
+        *n_parts = 0;
+        *part_stride = 0;
+        return small_down_launch(W, h, offsets, N, inv_perm, weights, T, k, y, yg, s);
+    }
     StreamArgs dn = stream_args_down(W, pl, h, offsets, N, slabs);
     dn.part_stride = (size_t)N * d;
     rc = stream_dispatch<1, false, false>(pl.KSWd, pl.Wd, s, dn);

@@ -72,7 +72,7 @@ int moe_ffn_f32_launch(const moe_weights* W, const float* xg, const int32_t* per
 
 bool moe_ffn_stream_supported(int d, int f);
 size_t moe_ffn_stream_workspace(int N, int E, int d, int f);
-int moe_ffn_stream_parts(int d, int f);  // reduction parts of the second projection (0: unsupported)
+int moe_ffn_stream_parts(int N, int d, int f);  // slabs the second projection leaves (0: unsupported)
 int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
                           const int32_t* perm, int k, const int32_t* offsets, int N, void* ws,
                           float* out, int* n_parts, hipStream_t s);
@@ -80,8 +80,8 @@ bool moe_ffn_stream_decode_supported(int T, int E, int k, int d, int f);
 int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const float* logits, int T,
                                  int k, int32_t* idx, float* weights, int32_t* counts,
                                  int32_t* offsets, int32_t* perm, int32_t* inv_perm, float* xg,
-                                 void* ws, const float** parts, int* n_parts, size_t* part_stride,
-                                 hipStream_t s);
+                                 void* ws, float* y, float* yg, const float** parts, int* n_parts,
+                                 size_t* part_stride, hipStream_t s);
 
 size_t moe_ffn_grouped_workspace(int N, int E, int d, int f);
 int moe_ffn_grouped_plan(int N, int E, int d, int f, moe_ffn_plan_t* plan);  // fills the tile fields

@@ -57,7 +57,13 @@ def test_stream_path_ten_step_reductions(moe, d, f, T, xdt):
 @pytest.mark.parametrize("T,d,f,E,k", [(1, 256, 512, 8, 2), (16, 256, 512, 8, 2), (7, 1024, 1792, 4, 2),
                                        (16, 512, 1024, 16, 4), (3, 2048, 3584, 8, 2), (5, 320, 640, 4, 2),
                                        (16, 128, 256, 3, 3), (9, 256, 1600, 16, 1), (8, 256, 512, 8, 8),
-                                       (4, 256, 7168, 8, 2)])
+                                       (4, 256, 7168, 8, 2),
+                                       # one to four routed rows: the second projection finishes its
+                                       # reduction and the combine in one kernel; f = 1600 leaves
+                                       # the waves of a row unequal shares of the reduction
+                                       (1, 256, 1600, 8, 1), (1, 512, 1600, 8, 3), (1, 512, 1600, 8, 2), (2, 256, 512, 8, 2),
+                                       (1, 1024, 7168, 8, 4), (2, 320, 640, 4, 1), (4, 256, 512, 4, 1),
+                                       (1, 4096, 2048, 8, 2), (1, 128, 14336, 8, 2)])
 def test_decode_layer_small_shapes(moe, T, d, f, E, k):
     """moe_decode_layer against the oracle and, bit for bit, against the four calls."""
     cfg = mi.small_config("dl", T, d, f, E, k, 1700 + T + d, w_dtype=mi.BF16, zipf_s=1.2)
@@ -71,6 +77,7 @@ def test_decode_layer_small_shapes(moe, T, d, f, E, k):
     torch.cuda.synchronize()
     _check_indices(out, ref)
     assert (to_host(out["xg"]) == li.x[ref["perm"] // k]).all()
+    assert not torch.isnan(out["yg"]).any() and not torch.isnan(out["y"]).any()
     e_yg, e_y = max_rel(to_host(out["yg"]), ref["yg"]), max_rel(to_host(out["y"]), ref["y"])
     print(f"decode_layer T={T} d={d} f={f} E={E} k={k}: counts={ref['counts'].tolist()} "
           f"err yg={e_yg:.3e} y={e_y:.3e}")
@@ -176,4 +183,19 @@ def test_expert_ffn_parts_sum_to_yg(moe):
     parts = torch.full((2, cfg.N, cfg.d), float("nan"), device="cuda")
     assert moe.moe_expert_ffn_parts(W, xg, offsets, parts) == 1
     assert torch.equal(parts[0], moe.moe_expert_ffn(W, xg, offsets))
+    W.free()
+    # one token: the second projection sums inside its workgroups and leaves one slab, even
+    # where more rows of the same shape leave several
+    cfg = mi.small_config("p1", 1, 512, 7168, 8, 2, 1903, w_dtype=mi.BF16)
+    li = mi.make_layer(cfg, threads=8)
+    W = pack_layer(li)
+    assert moe.moe_expert_ffn_plan(64, cfg.E, cfg.d, cfg.f)["n_parts"] > 1
+    assert moe.moe_expert_ffn_plan(cfg.N, cfg.E, cfg.d, cfg.f)["n_parts"] == 1
+    idx, _ = moe.moe_route(to_dev(li.logits), cfg.k)
+    _, offsets, _, _, xg = moe.moe_permute(idx, cfg.E, to_dev(li.x))
+    parts = torch.full((1, cfg.N, cfg.d), float("nan"), device="cuda")
+    assert moe.moe_expert_ffn_parts(W, xg, offsets, parts) == 1
+    assert torch.equal(parts[0], moe.moe_expert_ffn(W, xg, offsets))
+    ref = orc.layer(mi.to_f64(li.x), li.logits, li.w1, li.w3, li.w2, cfg.k)
+    assert max_rel(to_host(parts[0]), ref["yg"]) <= 1e-4
     W.free()
