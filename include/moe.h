@@ -225,6 +225,9 @@ int moe_combine_parts(const float* yg_parts, int n_parts, const int32_t* inv_per
  * tokens, where every launch is a few percent of the step): the first-projection kernel runs
  * the gating function and the per-expert batching in its prologue and reads the token rows
  * directly, the second projection leaves its reduction parts, and the combine adds them.
+ * With at most four routed rows (one token of a top-2 layer: Sec. 4.1, scenario (a)) the
+ * second projection finishes its reduction and the combine inside its workgroups: two
+ * launches.
  * Same results as moe_route + moe_permute + moe_expert_ffn + moe_combine: index outputs bit
  * for bit, y and yg in the same fixed summation order.
  *   x [T,d] fp32, logits [T,E] fp32; bf16 weights; 1 <= T <= 16, E <= 16, T*k <= 64 and a
@@ -238,6 +241,53 @@ int moe_decode_layer(const moe_weights_t* W, const float* x, const float* logits
                      int32_t* idx, float* weights, int32_t* counts, int32_t* offsets,
                      int32_t* perm, int32_t* inv_perm, float* xg, void* workspace,
                      size_t workspace_bytes, float* yg, float* y, void* stream);
+
+/*
+ * The expert layer of one transformer block on the residual stream, for decode steps of at
+ * most four routed rows (T*k <= 4), in two launches: moe_decode_layer's kernels, of which the
+ * first also derives the block's RMSNorm and router logits and the second also adds the
+ * residual and prepares the gating sums of the NEXT block (the non-expert work between two
+ * expert layers, Sec. 3.3 "Execution"), so that a stack of blocks needs no launch between
+ * them.  The gating sums of the rows x[t,:] against a router matrix w_gate [d,E] are
+ *     S[t,e] = sum_c x[t,c] * w_gate[c,e]   (e < E),      S[t,E] = sum_c x[t,c]^2
+ * kept as `shares` [n_shares][stride] fp32, stride = moe_gate_sums_stride(T, E), S[t,e] at
+ * t*(E+1)+e: share b holds the sums over a part of the features c, and the shares are added
+ * in order b = 0, 1, ... in a fixed tree (deterministic).  The call computes
+ *     scale[t]    = 1 / sqrt(S[t,E] / d + eps)                RMSNorm, unit gain
+ *     logits[t,e] = S[t,e] * scale[t]                         written to `logits`
+ *     h[t,:]      = x_in[t,:] * scale[t]                      the experts' input rows
+ *     routing and expert FFN of the rows h on `logits`, as moe_decode_layer
+ *     x_out[t,:]  = x_in[t,:] + y[t,:]
+ *     gate_sums_next = the d/16 shares (16 features each) of x_out against w_gate_next
+ * With gate_sums NULL, `logits` is an input and h = x_in (no scale).
+ *   x_in [T,d] fp32; gate_sums [n_shares][stride] fp32 or NULL, 1 <= n_shares <= 256
+ *   logits [T,E] fp32: out, or in when gate_sums is NULL
+ *   idx, weights, counts, offsets, perm, inv_perm: as moe_route / moe_permute, all written
+ *   workspace >= moe_expert_ffn_workspace(T*k, E, d, f, MOE_F32)
+ *   x_out [T,d] fp32 out; may be x_in itself (in place), no other overlap between arguments
+ *   w_gate_next [d,E] fp32 or NULL (then gate_sums_next is not written);
+ *   gate_sums_next [d/16][stride] fp32 out: pass it, with n_shares = d/16, to the next call
+ * MOE_ERR_UNSUPPORTED for fp32 weights, T*k > 4, E > 16, T*(E+1) > 32, d/16 above the number
+ * of compute units (or above 32 per wavefront of the first kernel), or a shape the STREAM
+ * family does not serve: use the
+ * separate calls then.
+ */
+int moe_decode_block(const moe_weights_t* W, const float* x_in, const float* gate_sums,
+                     int n_shares, float eps, float* logits, int T, int k, int32_t* idx,
+                     float* weights, int32_t* counts, int32_t* offsets, int32_t* perm,
+                     int32_t* inv_perm, void* workspace, size_t workspace_bytes, float* x_out,
+                     const float* w_gate_next, float* gate_sums_next, void* stream);
+/* HOST query: 1 if moe_decode_block serves these sizes on the current device, else 0. */
+int moe_decode_block_supported(int T, int E, int k, int d, int f, moe_dtype_t w_dtype);
+/*
+ * The gating sums of the first block of a stack: one share (n_shares = 1) with the sums over
+ * all d features of the rows x [T,d] against w_gate [d,E]; E <= 16 (MOE_ERR_UNSUPPORTED
+ * above).  sums [moe_gate_sums_stride(T, E)] fp32 out, 16-byte aligned.
+ */
+int moe_gate_sums(const float* x, const float* w_gate, int T, int d, int E, float* sums,
+                  void* stream);
+/* HOST: floats per share: 32, one 128-byte line (0 for invalid sizes). */
+size_t moe_gate_sums_stride(int T, int E);
 
 /*
  * Support steps of the layer-stack workload (non-expert glue the paper keeps

@@ -21,10 +21,11 @@ EXPORTS = ("moe_status_string", "moe_route", "moe_permute", "moe_weights_pack",
            "moe_weights_free", "moe_weights_bytes", "moe_expert_ffn_workspace",
            "moe_expert_ffn", "moe_expert_ffn_path", "moe_expert_ffn_plan",
            "moe_expert_ffn_parts", "moe_expert_ffn_tokens", "moe_expert_ffn_noalloc", "moe_expert_ffn_noalloc_max_bytes",
-           "moe_combine", "moe_combine_parts", "moe_decode_layer",
+           "moe_combine", "moe_combine_parts", "moe_decode_layer", "moe_decode_block",
            "moe_rmsnorm", "moe_router_logits", "moe_residual_add", "moe_route_permute",
            "moe_norm_route_permute", "moe_combine_residual", "moe_combine_norm_route_permute",
-           "moe_rmsnorm_router_logits")
+           "moe_rmsnorm_router_logits", "moe_gate_sums", "moe_gate_sums_stride",
+           "moe_decode_block_supported")
 PROBE_EXPORTS = ("moe_set_ffn_mid_event", "moe_mfma_rate_probe", "moe_hbm_read_probe")
 ORCH_EXPORTS = ("moe_orch_place", "moe_orch_hit_rate", "moe_orch_decide", "moe_orch_cpu_expert_ffn",
                 "moe_orch_layer_create", "moe_orch_layer_free", "moe_orch_calibrate",
@@ -113,6 +114,15 @@ def lib():
         L.moe_combine_parts.restype = C.c_int
         L.moe_decode_layer.argtypes = [vp, vp, vp, i32, i32] + [vp] * 8 + [C.c_size_t, vp, vp, vp]
         L.moe_decode_layer.restype = C.c_int
+        L.moe_decode_block.argtypes = ([vp, vp, vp, i32, f32, vp, i32, i32] + [vp] * 7 +
+                                       [C.c_size_t, vp, vp, vp, vp])
+        L.moe_decode_block.restype = C.c_int
+        L.moe_decode_block_supported.argtypes = [i32] * 6
+        L.moe_decode_block_supported.restype = C.c_int
+        L.moe_gate_sums.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        L.moe_gate_sums.restype = C.c_int
+        L.moe_gate_sums_stride.argtypes = [i32, i32]
+        L.moe_gate_sums_stride.restype = C.c_size_t
         dp = C.POINTER(C.c_double)
         L.moe_orch_place.argtypes = [vp, i32, i32, i32, vp]
         L.moe_orch_hit_rate.argtypes = [vp, vp, i32, i32]
@@ -390,6 +400,81 @@ def moe_decode_layer(W: "PackedWeights", x: torch.Tensor, logits: torch.Tensor, 
                 xg=xg, yg=yg, y=y)
 
 
+def moe_decode_block_supported(T: int, E: int, k: int, d: int, f: int, w_dtype: int = MOE_BF16) -> bool:
+    """Does moe_decode_block serve these sizes on the current device (host query)?"""
+    return bool(lib().moe_decode_block_supported(T, E, k, d, f, w_dtype))
+
+
+def moe_gate_sums_stride(T: int, E: int) -> int:
+    """Floats per share of the gating sums (host query)."""
+    return int(lib().moe_gate_sums_stride(T, E))
+
+
+def moe_gate_sums(x: torch.Tensor, w_gate: torch.Tensor, sums=None, stream=None):
+    """x [T,d], w_gate [d,E] -> one share [stride] of the gating sums: x . w_gate[:, e] at
+    t*(E+1)+e and sum(x^2) at t*(E+1)+E (the input of the first moe_decode_block of a stack)."""
+    _dev(x, torch.float32, "x")
+    _dev(w_gate, torch.float32, "w_gate")
+    T, d = x.shape
+    E = w_gate.shape[1]
+    if sums is None:
+        sums = torch.zeros(moe_gate_sums_stride(T, E), dtype=torch.float32, device=x.device)
+    _check(lib().moe_gate_sums(_ptr(x), _ptr(w_gate), T, d, E, _ptr(sums), _stream(stream)),
+           "moe_gate_sums")
+    return sums
+
+
+def moe_decode_block(W: "PackedWeights", x_in: torch.Tensor, k: int, gate_sums=None, n_shares: int = 0,
+                     eps: float = 1e-5, logits=None, idx=None, weights=None, out=None,
+                     workspace=None, x_out=None, w_gate_next=None, gate_sums_next=None,
+                     stream=None) -> dict:
+    """The expert layer of one block on the residual stream (T*k <= 4) in two launches:
+    x_out = x_in + layer(rmsnorm(x_in)), the RMSNorm scale and the router logits derived from
+    the gating sums `gate_sums` [n_shares, stride] (or, without them, layer(x_in) on the
+    given logits), and with w_gate_next the d/16 shares of the next block's gating sums.
+    `out` = (counts, offsets, perm, inv_perm)."""
+    _dev(x_in, torch.float32, "x_in")
+    T, d = x_in.shape
+    E = W.E
+    N = T * k
+    dev = x_in.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    if gate_sums is None:
+        _dev(logits, torch.float32, "logits")
+        n_shares = 0
+    else:
+        _dev(gate_sums, torch.float32, "gate_sums")
+        if n_shares <= 0:
+            n_shares = gate_sums.shape[0] if gate_sums.dim() == 2 else 1
+        if logits is None:
+            logits = torch.empty((T, E), **f32)
+    if idx is None:
+        idx = torch.empty((T, k), **i32)
+    if weights is None:
+        weights = torch.empty((T, k), **f32)
+    if out is None:
+        out = (torch.empty(E, **i32), torch.empty(E + 1, **i32), torch.empty(N, **i32),
+               torch.empty(N, **i32))
+    counts, offsets, perm, inv_perm = out[:4]
+    if workspace is None:
+        workspace = torch.empty(max(moe_expert_ffn_workspace(N, W.E, W.d, W.f, MOE_F32), 256),
+                                dtype=torch.uint8, device=dev)
+    if x_out is None:
+        x_out = torch.empty((T, d), **f32)
+    if w_gate_next is not None:
+        _dev(w_gate_next, torch.float32, "w_gate_next")
+        if gate_sums_next is None:
+            gate_sums_next = torch.empty((d // 16, moe_gate_sums_stride(T, E)), **f32)
+    _check(lib().moe_decode_block(C.c_void_p(W.handle), _ptr(x_in), _ptr(gate_sums), n_shares, eps,
+                                  _ptr(logits), T, k, _ptr(idx), _ptr(weights), _ptr(counts),
+                                  _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(workspace),
+                                  workspace.numel(), _ptr(x_out), _ptr(w_gate_next),
+                                  _ptr(gate_sums_next), _stream(stream)), "moe_decode_block")
+    return dict(idx=idx, w=weights, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm,
+                logits=logits, x_out=x_out, gate_sums_next=gate_sums_next)
+
+
 def moe_combine(yg: torch.Tensor, inv_perm: torch.Tensor, weights: torch.Tensor, y=None,
                 stream=None):
     """yg fp32 [N,d], inv_perm int32 [N], weights fp32 [T,k] -> y fp32 [T,d]."""
@@ -568,6 +653,10 @@ class StackBuffers:
         self.yg_parts = torch.empty((self.max_parts, N, d), **f32)
         self.yg = self.yg_parts[0]
         self.y = torch.empty((T, d), **f32)
+        # the two-launch block step (moe_decode_block): the shares of the gating sums of the
+        # current and of the next block
+        stride = moe_gate_sums_stride(T, E) if E <= 16 else 0
+        self.gate_sums = [torch.zeros((max(d // 16, 1), max(stride, 4)), **f32) for _ in range(2)]
 
 
 def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=None,
@@ -579,8 +668,9 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
     that receive a copy of every layer's router logits / expert indices.  on_layer(l)
     is called before each layer's expert FFN is enqueued (measurement hook).  fused=True
     uses the one-launch front end (T <= 4) and combine+residual, and with seam=True also
-    folds each block's combine+residual into the next block's front end; fused=False the
-    separate calls.  The fused variants leave the second projection's reduction parts
+    folds each block's combine+residual into the next block's front end -- or, with at most
+    four routed rows, runs every block as the two launches of moe_decode_block; fused=False
+    the separate calls.  The fused variants leave the second projection's reduction parts
     unsummed and add them inside the combine (no separate launch)."""
     _dev(x, torch.float32, "x")
     T, d = x.shape
@@ -589,6 +679,26 @@ def moe_stack_forward(layers, x: torch.Tensor, k: int, eps: float = 1e-5, bufs=N
         bufs = StackBuffers(T, W0.E, k, d, W0.f, x.device)
     fused_gate = fused and T <= 4 and W0.E <= 16
     seam = seam and fused_gate
+    if seam and W0.dtype == MOE_BF16 and moe_decode_block_supported(T, W0.E, k, d, W0.f):
+        # at most four routed rows: two launches per block, nothing between two blocks
+        moe_gate_sums(x, layers[0][1], bufs.gate_sums[0], stream=stream)
+        n_shares = 1
+        for li, (W, _) in enumerate(layers):
+            a, b = li & 1, (li + 1) & 1
+            rs = bufs.sets[a]
+            if on_layer is not None:
+                on_layer(li)
+            w_next = layers[li + 1][1] if li + 1 < len(layers) else None
+            moe_decode_block(W, x, k, gate_sums=bufs.gate_sums[a], n_shares=n_shares, eps=eps,
+                             logits=bufs.logits, idx=rs["idx"], weights=rs["w"], out=rs["perm_out"],
+                             workspace=bufs.ws, x_out=x, w_gate_next=w_next,
+                             gate_sums_next=bufs.gate_sums[b], stream=stream)
+            n_shares = d // 16
+            if logits_out is not None:
+                logits_out.append(bufs.logits.clone())
+            if idx_out is not None:
+                idx_out.append(rs["idx"].clone())
+        return x
     # the seam kernel adds at most 4 parts
     use_parts = fused and (not seam or bufs.max_parts <= 4)
     n_parts = 1

@@ -258,6 +258,43 @@ int moe_decode_layer(const moe_weights_t* W, const float* x, const float* logits
                                     yg, (hipStream_t)stream);
 }
 
+int moe_decode_block(const moe_weights_t* W, const float* x_in, const float* gate_sums,
+                     int n_shares, float eps, float* logits, int T, int k, int32_t* idx,
+                     float* weights, int32_t* counts, int32_t* offsets, int32_t* perm,
+                     int32_t* inv_perm, void* workspace, size_t workspace_bytes, float* x_out,
+                     const float* w_gate_next, float* gate_sums_next, void* stream) {
+    if (!W) return MOE_ERR_INVALID_ARG;
+    if (!tek_ok(T, W->E, k) || T < 1) return MOE_ERR_INVALID_ARG;
+    if (!x_in || !logits || !idx || !weights || !counts || !offsets || !perm || !inv_perm || !x_out)
+        return MOE_ERR_INVALID_ARG;
+    if (gate_sums && (n_shares < 1 || !(eps >= 0.f) || !moe_aligned16(gate_sums)))
+        return MOE_ERR_INVALID_ARG;
+    if (w_gate_next && (!gate_sums_next || !moe_aligned16(gate_sums_next))) return MOE_ERR_INVALID_ARG;
+    if (!moe_aligned16(x_in) || !moe_aligned16(x_out) || !moe_aligned16(logits) ||
+        !moe_aligned16(idx) || !moe_aligned16(weights))
+        return MOE_ERR_INVALID_ARG;
+    if (W->dtype != MOE_BF16 || !moe_ffn_stream_block_supported(T, W->E, k, W->d, W->f))
+        return MOE_ERR_UNSUPPORTED;
+    if (gate_sums && n_shares > W->d / 16 && n_shares > 1) return MOE_ERR_INVALID_ARG;
+    const int N = T * k;
+    if (!workspace || (((uintptr_t)workspace) & 255u)) return MOE_ERR_WORKSPACE;
+    if (workspace_bytes < moe_expert_ffn_workspace(N, W->E, W->d, W->f, MOE_F32))
+        return MOE_ERR_WORKSPACE;
+    // x_out may be x_in itself (every element is read and written by the same lane), nothing else
+    const size_t xb = (size_t)T * W->d * sizeof(float), lb = (size_t)T * W->E * sizeof(float);
+    const size_t share = (size_t)moe_ffn_stream_gate_stride(T, W->E) * sizeof(float);
+    const size_t sb_in = share * (size_t)(gate_sums ? n_shares : 0), sb_out = share * (size_t)(W->d / 16);
+    if (x_out != x_in && ranges_overlap(x_in, xb, x_out, xb)) return MOE_ERR_INVALID_ARG;
+    if (ranges_overlap(logits, lb, weights, (size_t)N * 4) || ranges_overlap(x_out, xb, logits, lb) ||
+        ranges_overlap(gate_sums, sb_in, gate_sums_next, sb_out) ||
+        ranges_overlap(x_out, xb, gate_sums_next, sb_out) || ranges_overlap(x_out, xb, gate_sums, sb_in) ||
+        ranges_overlap(logits, lb, gate_sums_next, sb_out) || ranges_overlap(logits, lb, gate_sums, sb_in))
+        return MOE_ERR_INVALID_ARG;
+    return moe_ffn_stream_block_launch(W, x_in, gate_sums, n_shares, eps, logits, T, k, idx, weights,
+                                       counts, offsets, perm, inv_perm, workspace, x_out, w_gate_next,
+                                       gate_sums_next, (hipStream_t)stream);
+}
+
 int moe_combine(const float* yg, const int32_t* inv_perm, const float* weights, int T, int k,
                 int d, float* y, void* stream) {
     if (T < 0 || k < 1 || k > MOE_MAX_K || (long long)T * k >= MOE_MAX_N || !dims_ok(d))
@@ -281,7 +318,7 @@ int moe_router_logits(const float* h, const float* w_gate, int T, int d, int E, 
     if (T == 0) return MOE_OK;
     if (!h || !w_gate || !logits) return MOE_ERR_INVALID_ARG;
     if (moe_norm_logits_supported(E) && moe_aligned16(h))
-        return moe_norm_logits_launch(false, h, w_gate, T, d, E, 0.f, nullptr, logits,
+        return moe_norm_logits_launch(false, h, w_gate, T, d, E, 0.f, nullptr, logits, nullptr,
                                       (hipStream_t)stream);
     return moe_router_logits_launch(h, w_gate, T, d, E, logits, (hipStream_t)stream);
 }
@@ -293,7 +330,28 @@ int moe_rmsnorm_router_logits(const float* x, const float* w_gate, int T, int d,
     if (!x || !w_gate || !h || !logits || !moe_aligned16(x) || !moe_aligned16(h))
         return MOE_ERR_INVALID_ARG;
     if (!moe_norm_logits_supported(E)) return MOE_ERR_UNSUPPORTED;
-    return moe_norm_logits_launch(true, x, w_gate, T, d, E, eps, h, logits, (hipStream_t)stream);
+    return moe_norm_logits_launch(true, x, w_gate, T, d, E, eps, h, logits, nullptr,
+                                  (hipStream_t)stream);
+}
+
+int moe_gate_sums(const float* x, const float* w_gate, int T, int d, int E, float* sums,
+                  void* stream) {
+    if (T < 0 || !dims_ok(d) || E < 1 || E > MOE_MAX_E) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !w_gate || !sums || !moe_aligned16(x) || !moe_aligned16(sums)) return MOE_ERR_INVALID_ARG;
+    if (!moe_norm_logits_supported(E)) return MOE_ERR_UNSUPPORTED;
+    return moe_norm_logits_launch(true, x, w_gate, T, d, E, 0.f, nullptr, nullptr, sums,
+                                  (hipStream_t)stream);
+}
+
+size_t moe_gate_sums_stride(int T, int E) {
+    if (T < 1 || E < 1 || E > MOE_MAX_E) return 0;
+    return (size_t)moe_ffn_stream_gate_stride(T, E);
+}
+
+int moe_decode_block_supported(int T, int E, int k, int d, int f, moe_dtype_t w_dtype) {
+    if (!tek_ok(T, E, k) || T < 1 || !dims_ok(d) || !dims_ok(f)) return 0;
+    return (w_dtype == MOE_BF16 && moe_ffn_stream_block_supported(T, E, k, d, f)) ? 1 : 0;
 }
 
 int moe_residual_add(float* x, const float* y, int T, int d, void* stream) {

@@ -53,13 +53,19 @@
 //    8 x 32 (128 tokens x 512 features): experts with up to ~128 rows, where the default
 //           tile is half empty -- twice the weight bytes per step, no padded matrix work.
 #define GG_THREADS 256
+#ifndef GG_NS
 #define GG_NS 8            // LDS stages of B fragments (one KiB per token block each)
+#endif
 // The weight fragments of step k are requested GG_LA steps earlier into a register ring that
 // is named statically, so the step loop is unrolled GG_U times (GG_LA < GG_U, reduction %
 // GG_U == 0; GG_LA <= GG_NS - 3, see the waits in the step).  Deeper rings (8 / 5 with 8
 // stages, 8 / 7 with 10 stages on the 192-row tile) measured no faster.
+#ifndef GG_U
 #define GG_U 4
+#endif
+#ifndef GG_LA
 #define GG_LA 3
+#endif
 #ifndef GG_WIDE_MAX_ROWS
 #define GG_WIDE_MAX_ROWS 96  // mean rows per expert up to which the 128 x 512 tile is used
 #endif

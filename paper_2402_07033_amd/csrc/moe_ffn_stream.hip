@@ -60,7 +60,44 @@ struct StreamArgs {
     int32_t* perm;        // [T*k]
     int32_t* inv_perm;    // [T*k]
     float* xg;            // [T*k,K] gathered rows, or null (the kernel itself does not need them)
+    // or, instead of logits: the shares of the RMSNorm and router sums of the token rows,
+    // [n_shares][gate_stride] with (t, e) at t*(E+1)+e = sum_c x[t,c]*w_gate[c,e] and
+    // (t, E) = sum_c x[t,c]^2 over the share's features.  Every wave adds the shares in
+    // order, derives 1/rms and the logits, and reads the rows scaled by 1/rms.
+    const float* gate_sums;
+    int n_shares, gate_stride;
+    float eps;
+    float* logits_out;    // [T,E] or null: the logits derived from the shares (workgroup 0)
 };
+
+#define GS_MAX_ITEMS 32                    // T * (E + 1) of the shares, at most
+#define GS_WAVE_ROWS 32                    // shares one wave adds
+
+// Adds the shares [row0, row1) (at most GS_WAVE_ROWS) for one wave with few instructions (the
+// first weight request of the kernel waits for this): lane r copies row r into LDS, then lane
+// `it` adds column `it` in row order.  s_rows: GS_WAVE_ROWS x GS_MAX_ITEMS floats of this
+// wave; s_out[it] receives the totals.
+__device__ __forceinline__ void gate_add_shares(const float* __restrict__ sums, int row0, int row1,
+                                                int stride, int items, int lane, float* s_rows,
+                                                float* s_out) {
+    const int nrows = row1 - row0;
+    if (lane < nrows) {
+        // a share is a whole 128-byte line: all of it is copied, whatever `items`
+        const float4* src = (const float4*)(sums + (size_t)(row0 + lane) * stride);
+        float4* dst = (float4*)(s_rows + lane * GS_MAX_ITEMS);
+        const float4 v0 = src[0], v1 = src[1], v2 = src[2], v3 = src[3], v4 = src[4], v5 = src[5],
+                     v6 = src[6], v7 = src[7];
+        dst[0] = v0; dst[1] = v1; dst[2] = v2; dst[3] = v3;
+        dst[4] = v4; dst[5] = v5; dst[6] = v6; dst[7] = v7;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane < items) {
+        float v = 0.f;
+        for (int r = 0; r < nrows; r++) v += s_rows[r * GS_MAX_ITEMS + lane];
+        s_out[lane] = v;
+    }
+}
 
 // rowmap (LDS, or null): source row of sorted row i -- the kernels that route in their own
 // prologue read the token rows directly.
@@ -68,11 +105,15 @@ template <int KSW, bool ACT_BF16>
 __device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 1 : 2],
                                                 const void* actp, int K, int row0, int rows,
                                                 int ks0, int lane, const int* rowmap,
-                                                const int32_t* perm, int perm_k) {
+                                                const int32_t* perm, int perm_k,
+                                                const float* row_scale) {
+#pragma clang fp contract(off)
     const int t = lane & 15, kq = lane >> 4;
     int src_row = row0 + t;
     if (rowmap && t < rows) src_row = rowmap[row0 + t];
     if (perm && t < rows) src_row = perm[row0 + t] / perm_k;
+    float sc = 1.0f;
+    if (!ACT_BF16 && row_scale && t < rows) sc = row_scale[src_row];
 #pragma unroll
     for (int s = 0; s < KSW; s++) {
         const size_t off = (size_t)src_row * K + (size_t)(ks0 + s) * 32 + kq * 8;
@@ -88,6 +129,13 @@ __device__ __forceinline__ void stream_load_act(bf16x8_t (&act)[KSW][ACT_BF16 ? 
                 x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
                 x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
             }
+            // the scale is applied here, outside the branch of the loads and without a branch
+            // of its own: a use of the loaded values inside it would make every step wait for
+            // its own loads before the next step's are issued (sc is 1 without a scale: exact).
+            // The product is rounded to fp32 before the split below uses it, as if the scaled
+            // row had been stored (hence no contraction in this function).
+#pragma unroll
+            for (int j = 0; j < 8; j++) x[j] *= sc;
             unsigned hi[8], lo[8];
 #pragma unroll
             for (int j = 0; j < 8; j++) {
@@ -156,9 +204,14 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
     static_assert(R >= 1 && R <= 16 && NL % R == 0, "the ring depth must divide the loads per unit");
     __shared__ int s_tiles[ST_MAX_WAVES][3][ST_MAX_TILES];  // per wave: expert, first row, rows
     __shared__ f32x4_t s_red[2][ST_MAX_WAVES][NMAT][64];
+    static_assert(!GATE || sizeof(f32x4_t) * 2 * NMAT * 64 >= sizeof(float) * GS_WAVE_ROWS * GS_MAX_ITEMS,
+                  "an eighth of s_red holds a wave's rows of the shares");
     // per wave (GATE): expert id of every slot, its sorted position, source token of every
     // sorted row
     __shared__ int s_gate[GATE ? ST_MAX_WAVES : 1][3][GATE_WAVE_MAX_N];
+    // per wave (GATE, shares given): the summed shares, 1/rms per token, the logits
+    __shared__ float s_gsum[GATE ? ST_MAX_WAVES : 1][3][64];
+    __shared__ float s_gpart[GATE ? ST_MAX_WAVES : 1][GS_MAX_ITEMS];  // the waves' parts of the shares
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -168,6 +221,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
     int* s_trn = s_tiles[wave][2];
     int lo = 0, hi = 0;
     const int* rowmap = nullptr;
+    const float* row_scale = nullptr;  // [T] in LDS: token row t is multiplied by it first
     if (GATE) {
         // gating function and per-expert batching (Sec. 3.3 "Execution"; Algorithm 1's
         // inp_size), every wave for itself: no workgroup barrier before the first weight
@@ -176,7 +230,43 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
         int* s_pos = s_gate[wave][1];
         int* s_src = s_gate[wave][2];
         const bool writer = (blockIdx.x == 0 && wave == 0);
-        gate_route_wave(a.logits, a.T, a.E, a.k, lane, s_idx, writer, a.idx, a.weights);
+        const float* lg = a.logits;
+        if (a.gate_sums) {
+            float* s_sum = s_gsum[wave][0];
+            float* s_inv = s_gsum[wave][1];
+            float* s_lg = s_gsum[wave][2];
+            // every wave adds its part of the shares (each share is then loaded once per
+            // workgroup), the waves' parts are added in wave order by every wave for itself
+            const int items = a.T * (a.E + 1);
+            const int per_w = (a.n_shares + a.W - 1) / a.W;
+            const int row0 = wave * per_w;
+            const int row1 = (row0 + per_w) < a.n_shares ? (row0 + per_w) : a.n_shares;
+            // (the reduction buffer is idle until the first unit is finished)
+            gate_add_shares(a.gate_sums, row0, row1, a.gate_stride, items, lane,
+                            (float*)s_red + wave * (GS_WAVE_ROWS * GS_MAX_ITEMS), s_gpart[wave]);
+            __syncthreads();
+            if (lane < items) {
+                float v = s_gpart[0][lane];
+                for (int w = 1; w < a.W; w++) v += s_gpart[w][lane];
+                s_sum[lane] = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < a.T) s_inv[lane] = 1.0f / sqrtf(s_sum[lane * (a.E + 1) + a.E] / (float)a.K + a.eps);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < a.T * a.E) {
+                const int tok = lane / a.E, ex = lane % a.E;
+                const float v = s_sum[tok * (a.E + 1) + ex] * s_inv[tok];
+                s_lg[lane] = v;
+                if (writer && a.logits_out) a.logits_out[lane] = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            lg = s_lg;
+            row_scale = s_inv;
+        }
+        gate_route_wave(lg, a.T, a.E, a.k, lane, s_idx, writer, a.idx, a.weights);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         const int off = permute_indices_wave(s_idx, a.N, a.E, a.counts, a.offsets_out, a.perm,
@@ -242,7 +332,7 @@ __global__ __launch_bounds__(512) void stream_kernel(StreamArgs a) {
         const int row0 = s_tr0[tile], rows = s_trn[tile];
         if (tile != cur_tile || part != cur_part) {
             stream_load_act<KSW, ACT_BF16>(act, a.act, a.K, row0, rows, part * part_ks + wave_ks,
-                                           lane, rowmap, a.row_perm, a.row_k);
+                                           lane, rowmap, a.row_perm, a.row_k, row_scale);
             cur_tile = tile;
             cur_part = part;
         }
@@ -333,7 +423,9 @@ __global__ __launch_bounds__(256) void stream_reduce_kernel(const float4* __rest
 // loads in flight.  The sums are added in a fixed order: the result is deterministic.
 #define SM_MAX_ROWS 4
 #define SM_WAVES 8
+#ifndef SM_RING
 #define SM_RING 16
+#endif
 #define SM_STAGE_ITERS 8   // h groups (of 8 floats) per thread, at most
 
 struct SmallDownArgs {
@@ -345,8 +437,24 @@ struct SmallDownArgs {
     float* y;                 // [T,C] out (with inv_perm)
     float* yg;                // [N,C] out, or null
     int E, N, K, C, NB, KS, T, k;
+    // BLOCK instantiation: y = x_in + combine (the block's residual add), and, with
+    // w_gate_next, this workgroup's share of the next block's RMSNorm and router sums
+    const float* x_in;         // [T,C]
+    const float* w_gate_next;  // [C,E] fp32 or null
+    float* sums_next;          // [NB][gate_stride] out: see StreamArgs::gate_sums
+    int gate_stride;
 };
 
+#define SM_MAX_E 16                      // experts the BLOCK epilogue handles
+#define SM_ITEMS_MAX GS_MAX_ITEMS        // (token, expert or sum of squares) pairs
+#define SM_EXTRA_FLOATS (16 * SM_MAX_E + 4 * SM_ITEMS_MAX)
+
+// BLOCK: the transformer block's residual add and the next block's gating inputs in this
+// kernel's epilogue.  Every workgroup owns 16 features of the output rows: it adds the
+// residual and writes its 16 features' share of sum(y^2) and of y . w_gate_next; the next
+// block's first kernel adds the shares in workgroup order (deterministic).  No workgroup
+// waits for another and nothing is counted.
+template <bool BLOCK>
 __global__ __launch_bounds__(64 * SM_WAVES) void stream_down_small_kernel(SmallDownArgs a) {
     extern __shared__ __align__(16) unsigned char sm_raw[];
     // [N*KS*4] groups of {hi 16 B, lo 16 B}, then 32 B of zeros, then the waves' partial tiles
@@ -354,10 +462,14 @@ __global__ __launch_bounds__(64 * SM_WAVES) void stream_down_small_kernel(SmallD
     const int n_groups = a.N * a.KS * 4;
     u32x4_t* s_zero = s_h + 2 * (size_t)n_groups;
     f32x4_t* s_red = (f32x4_t*)(s_zero + 2);
+    // BLOCK: this workgroup's 16 rows of w_gate_next, the four lanes' shares, the totals
+    float* s_wg = (float*)(s_red + SM_WAVES * 64);
+    float* s_fin = s_wg + 16 * SM_MAX_E;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nb = blockIdx.x;
+    const bool gate_next = BLOCK && a.w_gate_next != nullptr;
 
     // h first (its loads are the oldest, so the wait for them does not include the weights)
     float4 hv[SM_STAGE_ITERS][2];
@@ -369,6 +481,8 @@ __global__ __launch_bounds__(64 * SM_WAVES) void stream_down_small_kernel(SmallD
             hv[i][1] = *(const float4*)(a.h + (size_t)g * 8 + 4);
         }
     }
+    float wgv = 0.f;
+    if (gate_next && tid < 16 * a.E) wgv = a.w_gate_next[(size_t)nb * 16 * a.E + tid];
 
     // this wave's row and share of its reduction steps
     const int wpr = SM_WAVES / a.N;  // waves per row
@@ -419,6 +533,7 @@ __global__ __launch_bounds__(64 * SM_WAVES) void stream_down_small_kernel(SmallD
         }
     }
     if (tid < 2) s_zero[tid] = u32x4_t{0u, 0u, 0u, 0u};
+    if (gate_next && tid < 16 * a.E) s_wg[tid] = wgv;
     __syncthreads();
 
     // B operand: column 0 carries the row, the other 15 columns are zero
@@ -445,35 +560,71 @@ __global__ __launch_bounds__(64 * SM_WAVES) void stream_down_small_kernel(SmallD
     __syncthreads();
 
     // lanes 0, 16, 32, 48 of wave 0 hold features 4*kq .. 4*kq+3 of column 0
-    if (wave != 0 || t != 0) return;
-    auto row_sum = [&](int row) -> float4 {
-        f32x4_t v = s_red[(row * wpr) * 64 + lane];
-        for (int w = 1; w < wpr; w++) v += s_red[(row * wpr + w) * 64 + lane];
-        return make_float4(v[0], v[1], v[2], v[3]);
-    };
-    const size_t col = (size_t)nb * 16 + 4 * kq;
-    if (a.yg)
-        for (int row = 0; row < a.N; row++) *(float4*)(a.yg + (size_t)row * a.C + col) = row_sum(row);
-    if (a.inv_perm) {
-        for (int tok = 0; tok < a.T; tok++) {
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int j = 0; j < a.k; j++) {
-                const float w = a.weights[tok * a.k + j];
-                int row = a.inv_perm[tok * a.k + j];
-                row = row < 0 ? 0 : (row >= a.N ? a.N - 1 : row);
-                const float4 v = row_sum(row);
-                acc.x += w * v.x;
-                acc.y += w * v.y;
-                acc.z += w * v.z;
-                acc.w += w * v.w;
+    const int items = a.T * (a.E + 1);  // BLOCK: (token, expert) sums and (token, sum of squares)
+    if (wave == 0) {
+        if (t == 0) {
+            auto row_sum = [&](int row) -> float4 {
+                f32x4_t v = s_red[(row * wpr) * 64 + lane];
+                for (int w = 1; w < wpr; w++) v += s_red[(row * wpr + w) * 64 + lane];
+                return make_float4(v[0], v[1], v[2], v[3]);
+            };
+            const size_t col = (size_t)nb * 16 + 4 * kq;
+            if (a.yg)
+                for (int row = 0; row < a.N; row++)
+                    *(float4*)(a.yg + (size_t)row * a.C + col) = row_sum(row);
+            if (a.inv_perm) {
+                for (int tok = 0; tok < a.T; tok++) {
+                    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int j = 0; j < a.k; j++) {
+                        const float w = a.weights[tok * a.k + j];
+                        int row = a.inv_perm[tok * a.k + j];
+                        row = row < 0 ? 0 : (row >= a.N ? a.N - 1 : row);
+                        const float4 v = row_sum(row);
+                        acc.x += w * v.x;
+                        acc.y += w * v.y;
+                        acc.z += w * v.z;
+                        acc.w += w * v.w;
+                    }
+                    if (BLOCK) {
+                        float4 xr = *(const float4*)(a.x_in + (size_t)tok * a.C + col);
+                        xr.x += acc.x; xr.y += acc.y; xr.z += acc.z; xr.w += acc.w;
+                        acc = xr;
+                    }
+                    *(float4*)(a.y + (size_t)tok * a.C + col) = acc;
+                    if (gate_next) {
+                        // this lane's four features' share of the token's sums
+                        const float xv[4] = {acc.x, acc.y, acc.z, acc.w};
+                        float* fin = s_fin + kq * SM_ITEMS_MAX + tok * (a.E + 1);
+                        float ss = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 4; i++) ss = fmaf(xv[i], xv[i], ss);
+                        fin[a.E] = ss;
+                        for (int ex = 0; ex < a.E; ex++) {
+                            float d = 0.f;
+#pragma unroll
+                            for (int i = 0; i < 4; i++) d = fmaf(xv[i], s_wg[(4 * kq + i) * a.E + ex], d);
+                            fin[ex] = d;
+                        }
+                    }
+                }
             }
-            *(float4*)(a.y + (size_t)tok * a.C + col) = acc;
+        }
+        if (gate_next) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (int it = lane; it < items; it += 64) {
+                float v = s_fin[it];
+#pragma unroll
+                for (int q = 1; q < 4; q++) v += s_fin[q * SM_ITEMS_MAX + it];
+                a.sums_next[(size_t)nb * a.gate_stride + it] = v;
+            }
         }
     }
 }
 
 static size_t small_down_lds(int N, int KS) {
-    return (size_t)N * KS * 4 * 32 + 32 + (size_t)SM_WAVES * 64 * sizeof(f32x4_t);
+    return (size_t)N * KS * 4 * 32 + 32 + (size_t)SM_WAVES * 64 * sizeof(f32x4_t) +
+           SM_EXTRA_FLOATS * sizeof(float);
 }
 
 // The small-row kernel serves a call when its rows fit in LDS and one workgroup per feature
@@ -487,9 +638,17 @@ static bool small_down_ok(int N, int d, int f) {
     return NB <= moe_num_cus();
 }
 
+// What the BLOCK instantiation needs beyond the plain kernel's arguments.
+struct SmallBlock {
+    const float* x_in;
+    const float* w_gate_next;
+    float* sums_next;
+    int gate_stride;
+};
+
 static int small_down_launch(const moe_weights* W, const float* h, const int32_t* offsets, int N,
                              const int32_t* inv_perm, const float* weights, int T, int k, float* y,
-                             float* yg, hipStream_t s) {
+                             float* yg, const SmallBlock* blk, hipStream_t s) {
     SmallDownArgs a = {};
     a.wfrag = (const u32x4_t*)W->w2;
     a.h = h;
@@ -500,16 +659,29 @@ static int small_down_launch(const moe_weights* W, const float* h, const int32_t
     a.yg = yg;
     a.E = W->E; a.N = N; a.K = W->f; a.C = W->d; a.NB = W->d / 16; a.KS = W->f / 32;
     a.T = T; a.k = k;
+    if (blk) {
+        a.x_in = blk->x_in;
+        a.w_gate_next = blk->w_gate_next;
+        a.sums_next = blk->sums_next;
+        a.gate_stride = blk->gate_stride;
+    }
     const size_t lds = small_down_lds(N, a.KS);
     static std::atomic<bool> attr_set[MOE_MAX_DEVICES];
     const int dev = moe_current_device();
     if (dev < 0) return MOE_ERR_HIP;
     if (!attr_set[dev].load(std::memory_order_relaxed)) {
-        MOE_HIP_TRY(hipFuncSetAttribute((const void*)stream_down_small_kernel,
+        MOE_HIP_TRY(hipFuncSetAttribute((const void*)stream_down_small_kernel<false>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        MOE_HIP_TRY(hipFuncSetAttribute((const void*)stream_down_small_kernel<true>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_set[dev].store(true, std::memory_order_relaxed);
     }
-    hipLaunchKernelGGL(stream_down_small_kernel, dim3((unsigned)a.NB), dim3(64 * SM_WAVES), lds, s, a);
+    if (blk)
+        hipLaunchKernelGGL(stream_down_small_kernel<true>, dim3((unsigned)a.NB), dim3(64 * SM_WAVES),
+                           lds, s, a);
+    else
+        hipLaunchKernelGGL(stream_down_small_kernel<false>, dim3((unsigned)a.NB), dim3(64 * SM_WAVES),
+                           lds, s, a);
     return moe_launch_status();
 }
 
@@ -655,7 +827,7 @@ int moe_ffn_stream_launch(const moe_weights* W, const void* xg, moe_dtype_t act_
     moe_record_mid_event(s);
     if (small_down_ok(N, d, f)) {
         if (n_parts) *n_parts = 1;
-        return small_down_launch(W, h, offsets, N, nullptr, nullptr, 0, 0, nullptr, out, s);
+        return small_down_launch(W, h, offsets, N, nullptr, nullptr, 0, 0, nullptr, out, nullptr, s);
     }
     const StreamArgs dn = stream_args_down(W, pl, h, offsets, N, pl.Pd > 1 ? slabs : out);
     rc = stream_dispatch<1, false, false>(pl.KSWd, pl.Wd, s, dn);
@@ -709,7 +881,7 @@ int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const flo
         *parts = nullptr;
         *n_parts = 0;
         *part_stride = 0;
-        return small_down_launch(W, h, offsets, N, inv_perm, weights, T, k, y, yg, s);
+        return small_down_launch(W, h, offsets, N, inv_perm, weights, T, k, y, yg, nullptr, s);
     }
     StreamArgs dn = stream_args_down(W, pl, h, offsets, N, slabs);
     dn.part_stride = (size_t)N * d;
@@ -718,4 +890,63 @@ int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const flo
     *n_parts = pl.Pd;
     *part_stride = (size_t)N * d;
     return rc;
+}
+
+bool moe_ffn_stream_block_supported(int T, int E, int k, int d, int f) {
+    // (a wave of the first kernel adds at most GS_WAVE_ROWS shares of GS_MAX_ITEMS sums)
+    StreamPlan pl;
+    return moe_ffn_stream_decode_supported(T, E, k, d, f) && stream_plan(d, f, pl) &&
+           E <= SM_MAX_E && T * (E + 1) <= GS_MAX_ITEMS && T * E <= 64 &&
+           d / 16 <= GS_WAVE_ROWS * pl.Wu && small_down_ok(T * k, d, f);
+}
+
+// A share is one 128-byte line: the workgroups that write neighbouring shares sit on different
+// XCDs, and a line written from two L2s is written back in pieces.
+int moe_ffn_stream_gate_stride(int T, int E) {
+    (void)T;
+    (void)E;
+    return GS_MAX_ITEMS;
+}
+
+// One transformer block's expert layer on the residual stream in two launches: the first
+// projection derives the gating inputs from the shares (or takes the logits as given), routes
+// in its prologue and reads the token rows; the second finishes with the combine, the
+// residual add and the shares of the next block's gating sums.
+int moe_ffn_stream_block_launch(const moe_weights* W, const float* x_in, const float* gate_sums,
+                                int n_shares, float eps, float* logits, int T, int k, int32_t* idx,
+                                float* weights, int32_t* counts, int32_t* offsets, int32_t* perm,
+                                int32_t* inv_perm, void* ws, float* x_out, const float* w_gate_next,
+                                float* gate_sums_next, hipStream_t s) {
+    const int d = W->d, f = W->f, E = W->E, N = T * k;
+    StreamPlan pl;
+    if (!moe_ffn_stream_block_supported(T, E, k, d, f) || !stream_plan(d, f, pl))
+        return MOE_ERR_UNSUPPORTED;
+    if (gate_sums && (n_shares < 1 || n_shares > GS_WAVE_ROWS * pl.Wu)) return MOE_ERR_INVALID_ARG;
+    float* h = (float*)ws;
+    SmallBlock blk = {};
+    blk.x_in = x_in;
+    blk.w_gate_next = w_gate_next;
+    blk.sums_next = gate_sums_next;
+    blk.gate_stride = moe_ffn_stream_gate_stride(T, E);
+    StreamArgs up = stream_args_up(W, pl, x_in, nullptr, N, h);
+    up.logits = logits;
+    up.T = T;
+    up.k = k;
+    up.idx = idx;
+    up.weights = weights;
+    up.counts = counts;
+    up.offsets_out = offsets;
+    up.perm = perm;
+    up.inv_perm = inv_perm;
+    if (gate_sums) {
+        up.gate_sums = gate_sums;
+        up.n_shares = n_shares;
+        up.gate_stride = blk.gate_stride;
+        up.eps = eps;
+        up.logits_out = logits;
+    }
+    int rc = stream_dispatch<2, false, true>(pl.KSWu, pl.Wu, s, up);
+    if (rc != MOE_OK) return rc;
+    moe_record_mid_event(s);
+    return small_down_launch(W, h, offsets, N, inv_perm, weights, T, k, x_out, nullptr, &blk, s);
 }

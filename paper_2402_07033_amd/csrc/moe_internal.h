@@ -83,6 +83,14 @@ int moe_ffn_stream_decode_launch(const moe_weights* W, const float* x, const flo
                                  void* ws, float* y, float* yg, const float** parts, int* n_parts,
                                  size_t* part_stride, hipStream_t s);
 
+bool moe_ffn_stream_block_supported(int T, int E, int k, int d, int f);
+int moe_ffn_stream_gate_stride(int T, int E);  // floats per share of the gating sums
+int moe_ffn_stream_block_launch(const moe_weights* W, const float* x_in, const float* gate_sums,
+                                int n_shares, float eps, float* logits, int T, int k, int32_t* idx,
+                                float* weights, int32_t* counts, int32_t* offsets, int32_t* perm,
+                                int32_t* inv_perm, void* ws, float* x_out, const float* w_gate_next,
+                                float* gate_sums_next, hipStream_t s);
+
 size_t moe_ffn_grouped_workspace(int N, int E, int d, int f);
 int moe_ffn_grouped_plan(int N, int E, int d, int f, moe_ffn_plan_t* plan);  // fills the tile fields
 int moe_ffn_grouped_launch(const moe_weights* W, const void* xg, moe_dtype_t act_dtype,
@@ -128,7 +136,7 @@ int moe_router_logits_launch(const float* h, const float* w_gate, int T, int d, 
 int moe_residual_add_launch(float* x, const float* y, int T, int d, hipStream_t s);
 bool moe_norm_logits_supported(int E);
 int moe_norm_logits_launch(bool norm, const float* x, const float* w_gate, int T, int d, int E,
-                           float eps, float* h, float* logits, hipStream_t s);
+                           float eps, float* h, float* logits, float* sums, hipStream_t s);
 int moe_weights_pack_impl(const void* w1, const void* w3, const void* w2, int E, int d, int f,
                           moe_dtype_t w_dtype, moe_weights** out, hipStream_t s);
 int moe_weights_free_impl(moe_weights* W);

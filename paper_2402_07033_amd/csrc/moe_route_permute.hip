@@ -819,7 +819,8 @@ __global__ __launch_bounds__(NL_THREADS) void norm_logits_kernel(const float* __
                                                                   const float* __restrict__ w_gate,
                                                                   int T, int d, int E, float eps,
                                                                   float* __restrict__ h,
-                                                                  float* __restrict__ logits) {
+                                                                  float* __restrict__ logits,
+                                                                  float* __restrict__ sums) {
     static_assert(NL_TOK <= GATE_NORM_MAX_T, "gate_partial_sums holds GATE_NORM_MAX_T tokens");
     __shared__ float s_part[NL_THREADS / 64][NL_TOK * (GATE_MAX_E + 1)];
     __shared__ float s_inv[NL_TOK];
@@ -861,6 +862,7 @@ __global__ __launch_bounds__(NL_THREADS) void norm_logits_kernel(const float* __
         float v = 0.f;
         for (int w = 0; w < NL_THREADS / 64; w++) v += s_part[w][tid * (GATE_MAX_E + 1) + GATE_MAX_E];
         s_inv[tid] = NORM ? 1.0f / sqrtf(v / (float)d + eps) : 1.0f;
+        if (NORM && sums) sums[(size_t)(t0 + tid) * (E + 1) + E] = v;  // the raw sum of squares
     }
     __syncthreads();
     if (tid < Tl * GATE_MAX_E) {
@@ -868,10 +870,11 @@ __global__ __launch_bounds__(NL_THREADS) void norm_logits_kernel(const float* __
         if (e < E) {
             float v = 0.f;
             for (int w = 0; w < NL_THREADS / 64; w++) v += s_part[w][t * (GATE_MAX_E + 1) + e];
-            logits[(size_t)(t0 + t) * E + e] = NORM ? v * s_inv[t] : v;
+            if (logits) logits[(size_t)(t0 + t) * E + e] = NORM ? v * s_inv[t] : v;
+            if (NORM && sums) sums[(size_t)(t0 + t) * (E + 1) + e] = v;  // the raw dot product
         }
     }
-    if (NORM) {
+    if (NORM && h) {
         const int row_chunks = d / 4;
         for (int t = 0; t < Tl; t++) {
             const float sc = s_inv[t];
@@ -888,14 +891,16 @@ __global__ __launch_bounds__(NL_THREADS) void norm_logits_kernel(const float* __
 
 bool moe_norm_logits_supported(int E) { return E <= GATE_MAX_E; }
 
+// norm: h (if not null) is written too, and sums (if not null) receives the unscaled sums
+// [T][E+1]: x . w_gate[:, e] at e, sum(x^2) at E; logits may then be null
 int moe_norm_logits_launch(bool norm, const float* x, const float* w_gate, int T, int d, int E,
-                           float eps, float* h, float* logits, hipStream_t s) {
+                           float eps, float* h, float* logits, float* sums, hipStream_t s) {
     const unsigned grid = (unsigned)((T + NL_TOK - 1) / NL_TOK);
     if (norm)
         hipLaunchKernelGGL(norm_logits_kernel<true>, dim3(grid), dim3(NL_THREADS), 0, s, x, w_gate, T,
-                           d, E, eps, h, logits);
+                           d, E, eps, h, logits, sums);
     else
         hipLaunchKernelGGL(norm_logits_kernel<false>, dim3(grid), dim3(NL_THREADS), 0, s, x, w_gate, T,
-                           d, E, eps, h, logits);
+                           d, E, eps, h, logits, sums);
     return moe_launch_status();
 }

@@ -103,13 +103,16 @@ def test_argument_errors_return_before_any_launch(L):
 
 def test_ffn_plan_query(L):
     import paper_2402_07033_amd as m
-    pl = m.moe_expert_ffn_plan(2, 8, 4096, 14336)
+    pl = m.moe_expert_ffn_plan(32, 8, 4096, 14336)
     assert pl["path"] == m.MOE_FFN_STREAM and pl["n_parts"] == 4 and pl["up_tile_rows"] == 0
+    # one token's rows: the second projection finishes its reduction in one kernel
+    assert m.moe_expert_ffn_plan(2, 8, 4096, 14336)["n_parts"] == 1
     pl = m.moe_expert_ffn_plan(8192, 8, 4096, 14336)
     assert pl["path"] == m.MOE_FFN_GROUPED and pl["n_parts"] == 1
-    assert pl["up_tile_rows"] >= 128 and pl["down_tile_features"] >= 256
+    assert pl["up_tile_rows"] == 256 and pl["down_tile_features"] == 256
+    assert m.moe_expert_ffn_plan(512, 8, 4096, 14336, path=m.MOE_FFN_GROUPED)["up_tile_rows"] == 128
     assert m.moe_expert_ffn_plan(80, 8, 4096, 14336)["path"] == m.MOE_FFN_MID
-    assert m.moe_expert_ffn_plan(2, 16, 4096, 6400)["n_parts"] == 4
+    assert m.moe_expert_ffn_plan(32, 16, 4096, 6400)["n_parts"] == 4
     with pytest.raises(m.MoeError):
         m.moe_expert_ffn_plan(16, 8, 4096, 100)
 

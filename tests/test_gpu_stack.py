@@ -161,10 +161,13 @@ def test_seam_call_matches_separate_calls(moe, T, E, k, k_prev, d):
                                                wb, ob)
 
 
-def test_stack_seam_on_off_identical(moe):
-    """The stack with the combine folded into the next front end gives the same bits as
-    with the separate combine+residual launches."""
-    T, L, k = 1, 5, 2
+@pytest.mark.parametrize("T", [3, 1])
+def test_stack_seam_on_off(moe, T):
+    """T = 3: the stack with the combine folded into the next front end gives the same bits
+    as with the separate combine+residual launches.  T = 1 runs every block as the two
+    launches of moe_decode_block, whose sums are ordered differently: same routing, final
+    activations equal to rounding."""
+    L, k = 5, 2
     cfgs = [mi.small_config(f"m{l}", T, 512, 1024, 8, k, 4100 + l, w_dtype=mi.BF16) for l in range(L)]
     layers = []
     for cfg in cfgs:
@@ -172,6 +175,7 @@ def test_stack_seam_on_off_identical(moe):
         w_gate = mi.normal_f32(cfg.seed, 1, (cfg.d, cfg.E), cfg.d ** -0.5)
         layers.append((pack_layer(mi.LayerInputs(cfg, None, None, w1, w3, w2, w_gate)),
                        to_dev(w_gate)))
+    assert moe.moe_decode_block_supported(T, 8, k, 512, 1024) == (T == 1)
     x0 = mi.normal_f32(4100, 0, (T, 512))
     res = []
     for seam in (True, False):
@@ -180,11 +184,109 @@ def test_stack_seam_on_off_identical(moe):
         moe.moe_stack_forward(layers, xd, k, idx_out=idx, seam=seam)
         torch.cuda.synchronize()
         res.append((to_host(xd), [to_host(i) for i in idx]))
-    assert (res[0][0] == res[1][0]).all()
+    if T == 1:
+        assert max_rel(res[0][0], res[1][0].astype(np.float64)) <= 1e-5
+    else:
+        assert (res[0][0] == res[1][0]).all()
     for a, b in zip(res[0][1], res[1][1]):
         assert (a == b).all()
     for W, _ in layers:
         W.free()
+
+
+@pytest.mark.parametrize("T,k,E,d,f", [(1, 2, 8, 1024, 3584), (2, 2, 8, 512, 1024), (1, 4, 16, 2048, 1024),
+                                       (4, 1, 4, 256, 512), (1, 2, 8, 256, 1600), (1, 1, 3, 4096, 512),
+                                       (3, 1, 9, 320, 640), (2, 1, 15, 4096, 512)])
+def test_decode_block(moe, T, k, E, d, f):
+    """moe_decode_block against the fp64 oracle: RMSNorm scale and router logits derived from
+    the gating sums, layer output + residual, the next block's sums; against moe_decode_layer
+    (same bits on given logits); in place; and run to run."""
+    eps = 1e-5
+    cfg = mi.small_config("blk", T, d, f, E, k, 5200 + T + d + E, w_dtype=mi.BF16)
+    li = mi.make_layer(cfg, threads=4)
+    W = pack_layer(li)
+    assert moe.moe_decode_block_supported(T, E, k, d, f)
+    stride = moe.moe_gate_sums_stride(T, E)
+    assert stride == 32 and T * (E + 1) <= stride
+    x_in = (li.x * np.float32(1.7)).astype(np.float32)            # the residual stream
+    wg = mi.normal_f32(cfg.seed, 4, (d, E), d ** -0.5) * np.float32(3.0)
+    wg_next = mi.normal_f32(cfg.seed, 5, (d, E), d ** -0.5)
+    xd = to_dev(x_in)
+    # ---- the first block's sums: one share
+    s0 = moe.moe_gate_sums(xd, to_dev(wg))
+    x64 = x_in.astype(np.float64)
+    S_ref = np.concatenate([x64 @ wg.astype(np.float64), (x64 ** 2).sum(axis=1, keepdims=True)], axis=1)
+    S_gpu = to_host(s0)[:T * (E + 1)].reshape(T, E + 1)
+    assert np.max(np.abs(S_gpu - S_ref)) <= 1e-5 * np.max(np.abs(S_ref))
+    # ---- the block
+    out = moe.moe_decode_block(W, xd, k, gate_sums=s0, n_shares=1, eps=eps, w_gate_next=to_dev(wg_next))
+    torch.cuda.synchronize()
+    scale_ref = 1.0 / np.sqrt(S_ref[:, E] / d + eps)
+    lg_ref = S_ref[:, :E] * scale_ref[:, None]
+    lg_gpu = to_host(out["logits"])
+    e_l = np.max(np.abs(lg_gpu - lg_ref)) / max(1.0, np.max(np.abs(lg_ref)))
+    # routing on the logits the kernel reports (a near-tie may fall either way in fp32)
+    h64 = x64 * scale_ref[:, None]
+    ref = orc.layer(h64, lg_gpu, li.w1, li.w3, li.w2, k)
+    for key in ("idx", "counts", "offsets", "perm", "inv_perm"):
+        assert (to_host(out[key]) == ref[key]).all(), key
+    assert np.max(np.abs(to_host(out["w"]) - ref["w"])) <= 1e-6
+    x_out = to_host(out["x_out"])
+    assert not np.isnan(x_out).any()
+    e_x = max_rel(x_out, x64 + ref["y"])
+    # the next block's sums, in fp64 from the rows the kernel itself wrote, shares added up
+    xo64 = x_out.astype(np.float64)
+    Sn_ref = np.concatenate([xo64 @ wg_next.astype(np.float64), (xo64 ** 2).sum(axis=1, keepdims=True)], axis=1)
+    shares = to_host(out["gate_sums_next"]).astype(np.float64)
+    assert shares.shape == (d // 16, stride)
+    Sn_gpu = shares.sum(axis=0)[:T * (E + 1)].reshape(T, E + 1)
+    e_s = np.max(np.abs(Sn_gpu - Sn_ref)) / np.max(np.abs(Sn_ref))
+    print(f"decode_block T={T} k={k} E={E} d={d} f={f}: err x={e_x:.3e} logits={e_l:.3e} sums={e_s:.3e}")
+    assert e_x <= 1e-4 and e_l <= 2e-5 and e_s <= 1e-5
+    # chained: the next call derives its logits from these shares
+    nxt = moe.moe_decode_block(W, out["x_out"], k, gate_sums=out["gate_sums_next"], eps=eps)
+    scale_n = 1.0 / np.sqrt(Sn_ref[:, E] / d + eps)
+    lgn_ref = Sn_ref[:, :E] * scale_n[:, None]
+    assert np.max(np.abs(to_host(nxt["logits"]) - lgn_ref)) <= 2e-5 * max(1.0, np.max(np.abs(lgn_ref)))
+    assert nxt["gate_sums_next"] is None
+    # given logits, no scale: the same bits as moe_decode_layer plus the residual add
+    lg = to_dev(li.logits)
+    dl = moe.moe_decode_layer(W, xd, lg, k)
+    plain = moe.moe_decode_block(W, xd, k, logits=lg)
+    assert torch.equal(plain["x_out"], xd + dl["y"]) and torch.equal(plain["idx"], dl["idx"])
+    # in place; repeated: identical bits
+    for _ in range(5):
+        xi = to_dev(x_in.copy())
+        again = moe.moe_decode_block(W, xi, k, gate_sums=s0, eps=eps, x_out=xi, w_gate_next=to_dev(wg_next))
+        assert torch.equal(xi, out["x_out"]) and torch.equal(again["logits"], out["logits"])
+        n = T * (E + 1)   # (the padding floats of a share are never written)
+        assert torch.equal(again["gate_sums_next"][:, :n], out["gate_sums_next"][:, :n])
+    W.free()
+
+
+def test_decode_block_unsupported_and_errors(moe):
+    cfg = mi.small_config("blke", 4, 256, 512, 8, 2, 97, w_dtype=mi.BF16)
+    li = mi.make_layer(cfg, threads=1)
+    W = pack_layer(li)
+    x, lg = to_dev(li.x), to_dev(li.logits)
+    assert not moe.moe_decode_block_supported(4, 8, 2, 256, 512)      # 8 routed rows
+    assert not moe.moe_decode_block_supported(4, 16, 1, 256, 512)     # 4 * 17 sums
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_decode_block(W, x, 2, logits=lg)
+    assert ei.value.status == -2
+    x1, lg1 = x[:1].contiguous(), lg[:1].contiguous()
+    with pytest.raises(moe.MoeError) as ei:       # workspace too small
+        moe.moe_decode_block(W, x1, 2, logits=lg1, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == -3
+    sums = torch.zeros((16, 32), device="cuda")
+    with pytest.raises(moe.MoeError) as ei:       # the next sums over this call's sums
+        moe.moe_decode_block(W, x1, 2, gate_sums=sums, n_shares=16,
+                             w_gate_next=torch.zeros((256, 8), device="cuda"), gate_sums_next=sums)
+    assert ei.value.status == -1
+    with pytest.raises(moe.MoeError) as ei:       # more shares than a wave adds
+        moe.moe_decode_block(W, x1, 2, gate_sums=torch.zeros((300, 32), device="cuda"), n_shares=300)
+    assert ei.value.status == -1
+    W.free()
 
 
 def _run_stack(moe, cfgs, T, k, fused=True, free_running=True):
