@@ -49,6 +49,10 @@ TRAFFIC_SOURCES = {
                                                          r"gg_pack_kernel")),
     "e16_prefill_t4096": ("grouped_gemm_e16_prefill_t4096.txt",
                           (r"gg_gemm_kernel<true", r"gg_fixup_kernel<true", r"gg_pack_kernel")),
+    # stacks: per layer; the workload multiplies by its number of layers
+    "stack_t1": ("layer_stack_t1.txt", (r"stream_kernel<16, 2,",)),
+    "stack_t512": ("layer_stack_t512.txt", (r"gg_gemm_kernel<true", r"gg_fixup_kernel<true",
+                                            r"gg_pack_kernel")),
 }
 
 
@@ -369,7 +373,9 @@ def run_layer_workload(torch, moe, name, wl, sets, args, steps, warmup, host_w=N
                         second_projection_TFLOPs=T * K * 2 * D * F / (dn_ms * 1e-3) / 1e12,
                         whole_step_TFLOPs=whole, whole_step_frac=whole / MFMA_BF16_PEAK_TFLOPS)
     if step.one_call:
-        roofline["second_projection_note"] = "second_projection_ms includes the combine launch"
+        roofline["second_projection_note"] = (
+            "second_projection_ms includes the combine (inside the second kernel at T*k <= 4, "
+            "else its own launch)")
 
     result = {
         "metric": "MoE-layer tokens/s", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -455,8 +461,11 @@ def run_stack_workload(torch, moe, name, wl, layers, args, steps, warmup, host_w
     whole_gbs = all_bytes / (ms_per_step * 1e-3) / 1e9
     whole_tf = T * K * 6 * D * F * L / (ms_per_step * 1e-3) / 1e12
     label, plan = kernel_label(moe, T, moe.MOE_FFN_AUTO)
+    if moe.moe_decode_block_supported(T, E, K, D, F):
+        label = "RMSNorm scale + router logits + gating + " + label   # moe_decode_block's first kernel
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=None,
+                    frac=achieved / HBM_PEAK_GBS,
+                    traffic=(lambda t: None if t is None else t * L)(traffic_from_profile(name)),
                     kernel=label + ", summed over the layers",
                     kernel_ms=up_ms, active_experts_all_layers=n_active,
                     whole_step_GBs=whole_gbs, whole_step_frac=whole_gbs / HBM_PEAK_GBS,
