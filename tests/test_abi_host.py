@@ -99,6 +99,15 @@ def test_argument_errors_return_before_any_launch(L):
     # decode layer: null handle, and the plan query validates without a device
     assert L.moe_decode_layer(None, x, rest, 1, 2, *(rest,) * 6, None, rest, 1 << 20, None, h,
                               None) == INVALID
+    # block step and its gating sums: null handle / null pointers / unsupported sizes
+    assert L.moe_decode_block(None, x, None, 0, C.c_float(1e-5), rest, 1, 2, *(rest,) * 6, rest,
+                              1 << 20, h, None, None, None) == INVALID
+    assert L.moe_gate_sums(None, rest, 1, 256, 8, rest, None) == INVALID
+    assert L.moe_gate_sums(x, rest, 1, 256, 24, rest, None) == -2      # more than 16 experts
+    assert L.moe_gate_sums_stride(1, 8) == 32 and L.moe_gate_sums_stride(0, 8) == 0
+    assert L.moe_decode_block_supported(1, 8, 2, 4096, 14336, 1) == 1
+    assert L.moe_decode_block_supported(1, 8, 2, 4096, 14336, 0) == 0  # fp32 weights
+    assert L.moe_decode_block_supported(4, 8, 2, 4096, 14336, 1) == 0  # eight routed rows
 
 
 def test_ffn_plan_query(L):

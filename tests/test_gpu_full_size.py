@@ -240,3 +240,41 @@ def test_decode_layer_full_size(moe, shape_weights, name):
     print(f"decode_layer {name}: err yg={e_yg:.3e} y={e_y:.3e}")
     assert e_yg <= TOL_BF16 and e_y <= TOL_BF16
     assert torch.equal(out["yg"], four["yg"]) and torch.equal(out["y"], four["y"])
+
+
+@pytest.mark.parametrize("name,shape_weights", [("decode_t1", "decode_t1"), ("e16_decode_t1", "e16_decode_t1")],
+                         indirect=["shape_weights"])
+def test_decode_block_full_size(moe, shape_weights, name):
+    """The two-launch block step at the full shapes (one token): the small-row second
+    projection is the kernel that runs (one slab), RMSNorm scale and logits from the gating
+    sums, layer output + residual and the next block's sums against fp64."""
+    cfg = mi.CONFIGS[name]
+    eps = 1e-5
+    T, E, k, d = cfg.T, cfg.E, cfg.k, cfg.d
+    assert moe.moe_decode_block_supported(T, E, k, d, cfg.f)
+    assert moe.moe_expert_ffn_plan(cfg.N, E, d, cfg.f)["n_parts"] == 1
+    x, _, _ = mi.make_activations(cfg)
+    x_in = (x * np.float32(2.5)).astype(np.float32)
+    wg = mi.normal_f32(cfg.seed, 7, (d, E), d ** -0.5) * np.float32(2.0)
+    wg_next = mi.normal_f32(cfg.seed, 8, (d, E), d ** -0.5)
+    xd = to_dev(x_in)
+    s0 = moe.moe_gate_sums(xd, to_dev(wg))
+    out = moe.moe_decode_block(shape_weights["W"], xd, k, gate_sums=s0, n_shares=1, eps=eps,
+                               w_gate_next=to_dev(wg_next))
+    torch.cuda.synchronize()
+    x64 = x_in.astype(np.float64)
+    scale = 1.0 / np.sqrt((x64 ** 2).mean(axis=1) + eps)
+    lg_ref = (x64 @ wg.astype(np.float64)) * scale[:, None]
+    lg_gpu = to_host(out["logits"])
+    assert np.max(np.abs(lg_gpu - lg_ref)) <= 2e-5 * max(1.0, np.max(np.abs(lg_ref)))
+    ref = orc.layer(x64 * scale[:, None], lg_gpu, shape_weights["w1"], shape_weights["w3"],
+                    shape_weights["w2"], k)
+    _check_index_outputs(out, ref)
+    x_out = to_host(out["x_out"])
+    e_x = max_rel(x_out, x64 + ref["y"])
+    xo64 = x_out.astype(np.float64)
+    Sn_ref = np.concatenate([xo64 @ wg_next.astype(np.float64), (xo64 ** 2).sum(axis=1, keepdims=True)], axis=1)
+    Sn_gpu = to_host(out["gate_sums_next"]).astype(np.float64).sum(axis=0)[:T * (E + 1)].reshape(T, E + 1)
+    e_s = np.max(np.abs(Sn_gpu - Sn_ref)) / np.max(np.abs(Sn_ref))
+    print(f"decode_block {name}: err x={e_x:.3e} sums={e_s:.3e}")
+    assert e_x <= TOL_BF16 and e_s <= 1e-5
