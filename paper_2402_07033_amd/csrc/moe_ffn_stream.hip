@@ -25,10 +25,16 @@
 //        its partial sums into its own slab [part][N][d] and a small kernel (or the
 //        consumer: the gate-weighted combine) adds the slabs in part order, so the result
 //        does not depend on the order in which workgroups finish.
+//   down, one to four routed rows (stream_down_small_kernel): the rows of h fit in LDS, one
+//        workgroup per block of 16 output features takes the block's whole reduction, and the
+//        gate-weighted combine happens in its epilogue: no slabs, nothing left to add.
 // The first-projection kernel can also run the gating function and the per-expert batching
 // of a decode step (T <= 16 tokens, at most 64 slots) in its own prologue, every wave for
 // itself, and then reads the activations straight from the token rows: one launch less and
-// no gathered copy (moe_decode_layer).
+// no gathered copy (moe_decode_layer).  For a stack of transformer blocks (moe_decode_block)
+// it further derives the block's RMSNorm scale and router logits from shares of the gating
+// sums that the small-row kernel of the block before left behind, together with the
+// residual add: two launches per block and none between blocks.
 #include <atomic>
 
 #include "moe_internal.h"
