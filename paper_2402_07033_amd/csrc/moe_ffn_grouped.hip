@@ -151,6 +151,82 @@ __device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offse
     return false;
 }
 
+// The experts' segments for the persistent GEMM, built once per workgroup and kept in LDS
+// (entry e: expert e; entries >= E hold no tiles).  A tile index is then decoded with LDS
+// reads and a ballot -- no global memory access, and in particular no wait on the vector
+// memory counter, which would also cover the operand loads in flight for the next tile.
+#define GG_SEG_LO 0     // first row
+#define GG_SEG_ROWS 1   // rows
+#define GG_SEG_NB 2     // 16-row blocks
+#define GG_SEG_TILES 3  // token tiles
+#define GG_SEG_BASE 4   // first logical tile index
+#define GG_SEG_BB 5     // first packed block
+#define GG_SEG_FIELDS 6
+
+// One wave fills the table (lane e: expert e); returns the number of logical tiles.
+__device__ __forceinline__ int gg_seg_table(const int32_t* __restrict__ offsets, int E, int N,
+                                            int NT, int TB, int lane, int (*tab)[64], bool write) {
+    // lo_e = clamp(offsets[e], lo_{e-1}, N) = min(N, running max of offsets[0..e], at least 0);
+    // hi_e = clamp(offsets[e+1], lo_e, N): the same clamping as gg_total_tiles
+    const int o0 = (lane < E) ? offsets[lane] : 0, o1 = (lane < E) ? offsets[lane + 1] : 0;
+    int run = o0 < 0 ? 0 : o0;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const int v = __shfl_up(run, dlt, 64);
+        if (lane >= dlt) run = run > v ? run : v;
+    }
+    int lo = run > N ? N : run;
+    int hi = o1 < lo ? lo : (o1 > N ? N : o1);
+    if (lane >= E) {
+        lo = 0;
+        hi = 0;
+    }
+    const int rows = hi - lo, nb = (rows + 15) / 16, tiles = (nb + TB - 1) / TB;
+    int inc_t = tiles * NT, inc_b = nb;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const int vt = __shfl_up(inc_t, dlt, 64), vb = __shfl_up(inc_b, dlt, 64);
+        if (lane >= dlt) {
+            inc_t += vt;
+            inc_b += vb;
+        }
+    }
+    if (write) {
+        tab[GG_SEG_LO][lane] = lo;
+        tab[GG_SEG_ROWS][lane] = rows;
+        tab[GG_SEG_NB][lane] = nb;
+        tab[GG_SEG_TILES][lane] = tiles;
+        tab[GG_SEG_BASE][lane] = inc_t - tiles * NT;
+        tab[GG_SEG_BB][lane] = inc_b - nb;
+    }
+    return __builtin_amdgcn_readlane(inc_t, 63);
+}
+
+// Logical tile index -> tile, from the table (same order as gg_decode_tile).
+__device__ __forceinline__ bool gg_decode_tile_tab(const int (*tab)[64], int lane, int NT, int TB,
+                                                   int L, TileInfo& ti) {
+    const int my_tiles = tab[GG_SEG_TILES][lane], my_base = tab[GG_SEG_BASE][lane];
+    const unsigned long long m = __ballot(my_tiles > 0 && L >= my_base && L < my_base + my_tiles * NT);
+    if (m == 0ull) return false;
+    const int e = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(m));
+    const int tiles = __builtin_amdgcn_readfirstlane(tab[GG_SEG_TILES][e]);
+    const int nb = __builtin_amdgcn_readfirstlane(tab[GG_SEG_NB][e]);
+    const int r = L - __builtin_amdgcn_readfirstlane(tab[GG_SEG_BASE][e]);
+    ti.nt = r / tiles;
+    ti.tis = r % tiles;
+    ti.si.e = e;
+    ti.si.row0 = __builtin_amdgcn_readfirstlane(tab[GG_SEG_LO][e]);
+    ti.si.rows = __builtin_amdgcn_readfirstlane(tab[GG_SEG_ROWS][e]);
+    ti.si.bbase = __builtin_amdgcn_readfirstlane(tab[GG_SEG_BB][e]);
+    ti.blk0 = ti.tis * TB;
+    ti.nblk = (nb - ti.blk0) < TB ? (nb - ti.blk0) : TB;
+    ti.k_lo = 0;
+    ti.klen = 0;  // filled in by the caller
+    ti.partial = false;
+    ti.piece = 0;
+    return true;
+}
+
 // Cut points of the left-over tiles' joint reduction (S = R tiles x KS steps) for the
 // workgroups of one XCD: workgroup j covers [cut(j), cut(j+1)).  Pieces are multiples of
 // `unit` steps (KS is one too) and no piece is shorter than the smallest multiple of `unit`
@@ -176,6 +252,15 @@ __device__ __forceinline__ int gg_piece_cut(int j, int S, int KS, int wgs, int u
 template <bool ANT>
 __device__ __forceinline__ u32x4_t gg_ld_a(const u32x4_t* p) {
     return ANT ? __builtin_nontemporal_load(p) : *p;
+}
+
+// The lane number, recomputed where it is used and invisible to the optimiser (which would
+// otherwise share it with the copy made at kernel start and keep that alive, or derive
+// per-lane addresses from it ahead of the main loop).
+__device__ __forceinline__ int gg_lane_opaque() {
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
 }
 
 // MFMA with the accumulator pinned to the accumulation registers: 256 of them
@@ -233,7 +318,9 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
     // left-over tiles are cut along the reduction instead, in equal pieces for all
     // workgroups; every piece stores its partial sums into scratch and gg_fixup_kernel adds
     // the pieces of a tile in a fixed order (then applies SiLU*mul, first projection).
-    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT, NBW);
+    __shared__ int s_seg[GG_SEG_FIELDS][64];
+    const int total = gg_seg_table(a.offsets, a.E, a.N, a.NT, NBW, lane, s_seg, wave == 0);
+    __syncthreads();
     const int per_xcd = (total + 7) / 8;
     const int xcd = blockIdx.x & 7;
     const int wgs = gridDim.x >> 3;
@@ -243,7 +330,9 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
     const bool split = a.split && (chunk % wgs) != 0;
     const int n_full = split ? chunk / wgs : (chunk - me + wgs - 1) / wgs;  // whole tiles I own
     // pieces of the left-over tiles (slots n_full*wgs ... chunk-1) for this workgroup
-    int pc_tile[2] = {0, 0}, pc_lo[2] = {0, 0}, pc_len[2] = {0, 0}, n_pieces = 0;
+    // (plain scalars, no arrays: an array indexed at run time would live in scratch memory, and
+    // every read of it would wait on the counter of the operand loads in flight)
+    int pc_tile0 = 0, pc_lo0 = 0, pc_len0 = 0, pc_tile1 = 0, pc_len1 = 0, n_pieces = 0;
     if (split) {
         const int R = chunk - n_full * wgs;
         const int S = R * a.KS;
@@ -251,14 +340,22 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
         if (c0 < c1) {
             const int rA = c0 / a.KS;
             const int endA = c1 < (rA + 1) * a.KS ? c1 : (rA + 1) * a.KS;
-            pc_tile[0] = rA; pc_lo[0] = c0 - rA * a.KS; pc_len[0] = endA - c0;
+            pc_tile0 = rA; pc_lo0 = c0 - rA * a.KS; pc_len0 = endA - c0;
             n_pieces = 1;
             if (c1 > endA) {
-                pc_tile[1] = rA + 1; pc_lo[1] = 0; pc_len[1] = c1 - endA;
+                pc_tile1 = rA + 1; pc_len1 = c1 - endA;  // starts at step 0 of its tile
                 n_pieces = 2;
             }
         }
     }
+    // uniform values, pinned to scalar registers (the compiler otherwise keeps them in a table
+    // in scratch memory for the selection below)
+    pc_tile0 = __builtin_amdgcn_readfirstlane(pc_tile0);
+    pc_lo0 = __builtin_amdgcn_readfirstlane(pc_lo0);
+    pc_len0 = __builtin_amdgcn_readfirstlane(pc_len0);
+    pc_tile1 = __builtin_amdgcn_readfirstlane(pc_tile1);
+    pc_len1 = __builtin_amdgcn_readfirstlane(pc_len1);
+    n_pieces = __builtin_amdgcn_readfirstlane(n_pieces);
     const int n_units = (MODE == 1) ? n_full : n_full + n_pieces;
     auto unit_at = [&](int n, TileInfo& ti) -> bool {
         if (n >= n_units) return false;
@@ -266,11 +363,17 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
         if (n < n_full) {
             sl = me + n * wgs;
         } else {
-            sl = n_full * wgs + pc_tile[n - n_full];
-            lo = pc_lo[n - n_full];
-            len = pc_len[n - n_full];
+            // first or second piece, selected by arithmetic (a two-way choice on n is turned
+            // into a table in scratch memory by the compiler)
+            const int first = (n == n_full) ? 1 : 0;
+            sl = n_full * wgs + pc_tile1 + first * (pc_tile0 - pc_tile1);
+            lo = first * pc_lo0;
+            len = pc_len1 + first * (pc_len0 - pc_len1);
         }
-        if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, NBW, xcd * per_xcd + sl, ti)) return false;
+        // (the lane number is recomputed here, opaquely, so that no address derived from it
+        // has to stay in a register through the main loop; see the epilogue)
+        const int lane_d = gg_lane_opaque();
+        if (!gg_decode_tile_tab(s_seg, lane_d, a.NT, NBW, xcd * per_xcd + sl, ti)) return false;
         ti.k_lo = lo;
         ti.klen = len;
         ti.partial = (n >= n_full);  // pieces always go through scratch and the fix-up
@@ -335,17 +438,16 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
         // receives the fragments of step k+LA.  fast: every look-ahead lies inside
         // the current tile, so there is nothing to decide (compile-time after inlining).
         auto step = [&](int k, u32x4_t(&Ac)[FRW], u32x4_t(&An)[FRW], const bool fast) {
-            // do the look-ahead requests exist (in this tile or the next one)?
-            const bool la_b = fast || has_next || (k + NS - 1 < KT);
-            const bool la_a = fast || has_next || (k + LA < KT);
-            const bool more = fast || has_next || (k + 1 < KT);
+            // The look-ahead requests carry no condition: behind the workgroup's last unit they
+            // re-read the first steps of that unit (snxt == scur then), into stages and
+            // registers that nothing reads any more.  With conditions the compiler cannot
+            // count the loads in flight and waits for all of them before the weights' use.
+            constexpr bool la_b = true, la_a = true, more = true;
             // The weights of step k were requested LA steps ago, after that step's requests
             // for stage k+NS-1-LA; requests retire in order, so with at most the last
             // LA-1 steps' worth still in flight they have arrived, and so have the stages
-            // requested before them (LA <= NS-3: up to stage k+2).  Once the stream has
-            // ended (last tile, no look-ahead) wait for everything.
-            if (la_b) GG_WAIT_VMCNT((LA - 1) * VREQ);
-            else GG_WAIT_VMCNT(0);
+            // requested before them (LA <= NS-3: up to stage k+2).
+            GG_WAIT_VMCNT((LA - 1) * VREQ);
             // One barrier per TWO steps: at an even step every wave has waited for its
             // shares of stages k+1 and k+2 (see above), so both are published here; and the
             // buffers refilled during steps k and k+1 (stages k-1 and k) were last read
@@ -406,7 +508,13 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
         // ---- epilogue of the current tile (the next tile's loads are in flight) ----
         // the compiler cannot see the MFMAs: cover the matrix-core write -> read hazard
         asm volatile("s_nop 15\n s_nop 15" ::: "memory");
-        const int t = lane & 15, fq = lane >> 4;  // token in block, feature quad
+        // The epilogue's per-lane addresses are derived from a copy of the lane number that the
+        // compiler cannot trace back to the one above: it would otherwise compute them before
+        // the main loop and keep them in registers through it -- registers the loop does not
+        // have (the reload of a spilled one is a scratch load, and the wait for it also covers
+        // every store of the epilogue and every operand load of the next tile).
+        const int lane_e = gg_lane_opaque();
+        const int t = lane_e & 15, fq = lane_e >> 4;  // token in block, feature quad
         // a piece's partial sums: [16*NBW rows][16*FROWS columns] fp32 in this workgroup's slot
         float* slot = a.part + (((size_t)xcd * wgs + me) * 2 + cur.piece) * (256 * 256) +
                       (size_t)t * (16 * FROWS) + (FRW * wave) * 16 + 4 * fq;
@@ -465,7 +573,12 @@ __device__ __forceinline__ void gg_gemm_body(const GroupedArgs& a) {
                 }
             }
         }
-        if (!has_next) break;
+        if (!has_next) {
+            // the unconditional look-ahead of the last steps is still in flight (some of it on
+            // its way into LDS): it must land before the workgroup gives its LDS back
+            GG_WAIT_VMCNT(0);
+            break;
+        }
         // advance: next becomes current; look one unit further ahead
         unit++;
         cur = nxt;
