@@ -108,50 +108,9 @@ struct TileInfo {
     int piece;  // 0 or 1: which of this workgroup's two partial-tile slots it writes
 };
 
-// Number of logical tiles = NT * sum_e ceil(M_e / (16 * TB)).
-__device__ __forceinline__ int gg_total_tiles(const int32_t* __restrict__ offsets, int E, int N,
-                                              int NT, int TB) {
-    int total = 0, prev = 0;
-    for (int e = 0; e < E; e++) {
-        const int lo = gg_clamp_off(offsets[e], prev, N);
-        const int hi = gg_clamp_off(offsets[e + 1], lo, N);
-        prev = lo;
-        total += ((hi - lo + 16 * TB - 1) / (16 * TB)) * NT;
-    }
-    return total;
-}
-
-// Logical tile index -> tile.  Logical order: expert, then feature tile, then token
-// tile (fastest), so that neighbouring indices share the same weight tile.
-__device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offsets, int E, int N,
-                                               int NT, int TB, int L, TileInfo& ti) {
-    int base = 0, bb = 0, prev = 0;
-    for (int e = 0; e < E; e++) {
-        const int lo = gg_clamp_off(offsets[e], prev, N);
-        const int hi = gg_clamp_off(offsets[e + 1], lo, N);
-        prev = lo;
-        const int nb = (hi - lo + 15) / 16;
-        const int tiles = (nb + TB - 1) / TB;
-        if (L < base + tiles * NT) {
-            const int r = L - base;
-            ti.nt = r / tiles;
-            ti.tis = r % tiles;
-            ti.si.e = e; ti.si.row0 = lo; ti.si.rows = hi - lo; ti.si.bbase = bb;
-            ti.blk0 = ti.tis * TB;
-            ti.nblk = (nb - ti.blk0) < TB ? (nb - ti.blk0) : TB;
-            ti.k_lo = 0;
-            ti.klen = 0;  // filled in by the caller
-            ti.partial = false;
-            ti.piece = 0;
-            return true;
-        }
-        base += tiles * NT;
-        bb += nb;
-    }
-    return false;
-}
-
-// The experts' segments for the persistent GEMM, built once per workgroup and kept in LDS
+// Logical tiles of a launch: NT * sum_e ceil(M_e / (16 * TB)), in the order expert, then
+// feature tile, then token tile (fastest), so that neighbouring indices share a weight tile.
+// The experts' segments are decoded once per workgroup into a table in LDS
 // (entry e: expert e; entries >= E hold no tiles).  A tile index is then decoded with LDS
 // reads and a ballot -- no global memory access, and in particular no wait on the vector
 // memory counter, which would also cover the operand loads in flight for the next tile.
@@ -166,8 +125,9 @@ __device__ __forceinline__ bool gg_decode_tile(const int32_t* __restrict__ offse
 // One wave fills the table (lane e: expert e); returns the number of logical tiles.
 __device__ __forceinline__ int gg_seg_table(const int32_t* __restrict__ offsets, int E, int N,
                                             int NT, int TB, int lane, int (*tab)[64], bool write) {
+    // offsets that do not ascend or leave [0, N] are clamped, as in the pack kernel:
     // lo_e = clamp(offsets[e], lo_{e-1}, N) = min(N, running max of offsets[0..e], at least 0);
-    // hi_e = clamp(offsets[e+1], lo_e, N): the same clamping as gg_total_tiles
+    // hi_e = clamp(offsets[e+1], lo_e, N)
     const int o0 = (lane < E) ? offsets[lane] : 0, o1 = (lane < E) ? offsets[lane + 1] : 0;
     int run = o0 < 0 ? 0 : o0;
 #pragma unroll
@@ -202,7 +162,7 @@ __device__ __forceinline__ int gg_seg_table(const int32_t* __restrict__ offsets,
     return __builtin_amdgcn_readlane(inc_t, 63);
 }
 
-// Logical tile index -> tile, from the table (same order as gg_decode_tile).
+// Logical tile index -> tile, from the table.
 __device__ __forceinline__ bool gg_decode_tile_tab(const int (*tab)[64], int lane, int NT, int TB,
                                                    int L, TileInfo& ti) {
     const int my_tiles = tab[GG_SEG_TILES][lane], my_base = tab[GG_SEG_BASE][lane];
@@ -629,16 +589,22 @@ __global__ __launch_bounds__(256) void gg_fixup_kernel(GroupedArgs a, int wgs, i
     __shared__ int s_n;
     constexpr int RS = 16 * FROWS;  // floats per row of a partial tile
     const int xcd = blockIdx.x / wgs, r = blockIdx.x % wgs;
-    const int total = gg_total_tiles(a.offsets, a.E, a.N, a.NT, a.TB);
+    // the segment table as in the GEMM: one parallel read of the offsets and two wave scans
+    // instead of a walk over the experts with one memory round trip each (most workgroups of
+    // this grid find nothing to do and should find out quickly)
+    __shared__ int s_seg[GG_SEG_FIELDS][64];
+    const int lane = threadIdx.x & 63;
+    const int total = gg_seg_table(a.offsets, a.E, a.N, a.NT, a.TB, lane, s_seg, threadIdx.x < 64);
     const int per_xcd = (total + 7) / 8;
     int chunk = total - xcd * per_xcd;
     chunk = chunk < 0 ? 0 : (chunk > per_xcd ? per_xcd : chunk);
-    if (chunk % wgs == 0) return;
+    if (chunk % wgs == 0) return;   // (uniform over the workgroup, as the returns below)
     const int n_full = chunk / wgs;
     const int R = chunk - n_full * wgs;
     if (r >= R) return;
+    __syncthreads();
     TileInfo ti;
-    if (!gg_decode_tile(a.offsets, a.E, a.N, a.NT, a.TB, xcd * per_xcd + n_full * wgs + r, ti)) return;
+    if (!gg_decode_tile_tab(s_seg, lane, a.NT, a.TB, xcd * per_xcd + n_full * wgs + r, ti)) return;
     // second projection: the tile's real rows; first: every row of its blocks (h is kept in
     // whole 16-row fragments, padding rows included)
     const int tile_max = 16 * a.TB;
