@@ -89,6 +89,37 @@ def test_decode_layer_small_shapes(moe, T, d, f, E, k):
     W.free()
 
 
+@pytest.mark.parametrize("T,E,k", [(16, 8, 2), (16, 16, 4), (8, 3, 3), (4, 5, 1), (2, 2, 2), (1, 8, 2)])
+def test_decode_gating_with_ties(moe, T, E, k):
+    """The gating inside the first-projection kernel (every wave routes for itself) on logits
+    with exact ties, signed zeros and all-equal rows: the indices of the oracle (larger logit
+    first, lower expert index among equals), bit for bit; the same through moe_decode_block."""
+    d, f = 256, 512
+    cfg = mi.small_config("tie", T, d, f, E, k, 2300 + T + E, w_dtype=mi.BF16)
+    li = mi.make_layer(cfg, threads=1)
+    rng = np.random.default_rng(23 * T + E)
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    lg[0, :] = lg[0, 0]                                # an all-equal row
+    if T > 1:
+        lg[1, : E // 2 + 1] = 0.0                      # zeros of both signs
+        lg[1, 0] = -0.0
+    if T > 2:
+        lg[2, E - 1] = lg[2, 0] = lg[2].max() + 1.0    # the first and the last expert tie at the top
+    ref_idx, ref_w = orc.route(lg, k)
+    W = pack_layer(li)
+    out = moe.moe_decode_layer(W, to_dev(li.x), to_dev(lg), k)
+    assert (to_host(out["idx"]) == ref_idx).all()
+    assert np.max(np.abs(to_host(out["w"]) - ref_w)) <= TOL_GATE
+    ref = orc.layer(mi.to_f64(li.x), lg, li.w1, li.w3, li.w2, k)
+    _check_indices(out, ref)
+    assert max_rel(to_host(out["y"]), ref["y"]) <= 1e-4
+    if moe.moe_decode_block_supported(T, E, k, d, f):
+        blk = moe.moe_decode_block(W, to_dev(li.x), k, logits=to_dev(lg))
+        assert (to_host(blk["idx"]) == ref_idx).all()
+        assert torch.equal(blk["x_out"], to_dev(li.x) + out["y"])
+    W.free()
+
+
 def test_decode_layer_unsupported_and_errors(moe):
     cfg = mi.small_config("dle", 4, 256, 512, 8, 2, 99, w_dtype=mi.BF16)
     li = mi.make_layer(cfg, threads=1)
